@@ -1,0 +1,125 @@
+/*
+ * ecrm.h -- C ABI of the MI355X (gfx950) implementation of the ECRM parameter-server update path.
+ *
+ * ECRM (arXiv 2104.01981) keeps, for every group of k embedding entries, one parity entry
+ * p = e_0 + ... + e_{k-1} (and one parity row of optimizer state), and keeps the parities current
+ * by "difference propagation": after the optimizer has been applied to an entry, the differences
+ * in entry and optimizer state are added to the parity (Sec. 3.2, 3.3).  This library performs
+ * that work for a batch of sparse updates on ONE GPU that holds all S servers' shards.
+ *
+ * Data model (all DEVICE memory, caller-owned, fp32, row-major, 16-byte aligned):
+ *   E [R][D]    embedding entries            A [R][D]    Adagrad accumulators (optimizer state)
+ *   PE[R/k][D]  parity entries               PA[R/k][D]  parity accumulators
+ *   load_data[S], load_parity[S]  u64: number of entry / parity updates that fell on each server
+ * Stripe g consists of rows k*g .. k*g+k-1; its parity lives on server g mod S and member j on
+ * server (g+1+j) mod S (rotating placement, Sec. 3.2).
+ *
+ * Every entry point returns ECRM_OK (0) or a negative error code; nothing throws, logs, or
+ * allocates device memory.  encode/route/update only ENQUEUE work on the caller's HIP stream
+ * (pass the hipStream_t as void*; NULL is the default stream) and never synchronise: operations
+ * take effect in stream order, which is also what guarantees that every difference of an earlier
+ * update has reached its parity before later work reads it (Sec. 3.5).  A context is not
+ * thread-safe; different contexts are independent.
+ */
+#ifndef ECRM_H
+#define ECRM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ecrm_ctx ecrm_ctx; /* opaque; host memory only */
+
+enum {
+    ECRM_OK = 0,
+    ECRM_EINVAL = -1,    /* bad argument or configuration                                  */
+    ECRM_ENOTBOUND = -2, /* tables not bound yet                                           */
+    ECRM_ESCRATCH = -3,  /* scratch buffer missing, misaligned or too small                */
+    ECRM_EBATCH = -4,    /* n exceeds config.max_batch                                     */
+    ECRM_EKEYRANGE = -5, /* a key >= rows was seen on the device (reported by ecrm_status) */
+    ECRM_EHIP = -6       /* a HIP runtime call failed                                      */
+};
+
+enum { ECRM_OPT_ADAGRAD = 0 };
+
+typedef struct {
+    uint64_t rows;      /* R: k <= R <= 2^32 - 4096, multiple of k                              */
+    uint32_t dim;       /* D: floats per entry, multiple of 4, 4..1024 (the paper uses 128, 256) */
+    uint32_t k;         /* data entries per parity, 1..64 (paper: 2, 4, 10); r is fixed to 1     */
+    uint32_t servers;   /* S: k+1 <= S <= 1024 (paper: 5)                                        */
+    uint32_t optimizer; /* ECRM_OPT_ADAGRAD: the update rule printed in Sec. 3.3.1               */
+    float lr;           /* learning rate, used as its exact fp32 value                           */
+    float eps;          /* Adagrad epsilon (under the square root), >= 0                         */
+    uint64_t max_batch; /* largest n ever passed to ecrm_update, 1 .. 2^31 (sizes the scratch)   */
+} ecrm_config;
+
+/* Validates the configuration and creates a host-side context.  No device memory is touched. */
+int ecrm_create(const ecrm_config *cfg, ecrm_ctx **out);
+
+/* Frees the host-side context only; bound device buffers are never touched. NULL is allowed. */
+void ecrm_destroy(ecrm_ctx *ctx);
+
+/* Sizes in bytes: one data table (R*D*4), one parity table (R/k*D*4; the memory overhead of the
+ * code is therefore (k+1)/k, Sec. 2.4 / 3.1), and the scratch buffer ecrm_bind needs. */
+size_t ecrm_data_bytes(const ecrm_ctx *ctx);
+size_t ecrm_parity_bytes(const ecrm_ctx *ctx);
+size_t ecrm_scratch_bytes(const ecrm_ctx *ctx);
+
+/* Attaches caller-owned device buffers.  scratch must be 256-byte aligned and at least
+ * ecrm_scratch_bytes() long; its contents are private to the library while bound.  The load
+ * counters are accumulated into, never cleared.  Returns EINVAL for a NULL / misaligned table,
+ * ESCRATCH for the scratch buffer. */
+int ecrm_bind(ecrm_ctx *ctx, float *E, float *A, float *PE, float *PA,
+              uint64_t *load_data, uint64_t *load_parity, void *scratch, size_t scratch_bytes);
+
+/* Sum encoder with r = 1 (Sec. 3.2 "Encoder and decoder"): PE[g] = sum_j E[k*g+j], PA likewise,
+ * accumulated in fp64 and rounded once.  Run once before training (Sec. 3.1). */
+int ecrm_encode(ecrm_ctx *ctx, void *hip_stream);
+
+/* Rotating parity placement (Sec. 3.2) for n keys: stripe = key / k, member = key % k,
+ * data_srv = (stripe+1+member) % S, parity_srv = stripe % S.  All pointers are device memory of
+ * n elements; any output pointer may be NULL.  Keys >= rows raise the sticky EKEYRANGE status and
+ * leave their outputs unwritten. */
+int ecrm_route(ecrm_ctx *ctx, const uint64_t *keys, uint64_t n, uint64_t *stripe, uint32_t *member,
+               uint32_t *data_srv, uint32_t *parity_srv, void *hip_stream);
+
+/* One batch of n sparse updates (keys[i] = dense row id, grads[i][0..D) = its gradient), device
+ * pointers, read-only.  Per entry, updates are applied in arrival (index) order:
+ *     A[x] += g*g ;  E[x] -= lr / sqrt(A[x] + eps) * g            (Adagrad, Sec. 3.3.1)
+ * and the resulting differences in E[x] and A[x] are added to PE[x/k] and PA[x/k]
+ * (difference propagation, Sec. 3.3.2); load_data / load_parity count one update per item on the
+ * entry's and the parity's server (Sec. 3.6).  Arithmetic inside the call is carried in fp64 and
+ * every touched element is rounded to fp32 once.  If any key >= rows, NOTHING of this batch is
+ * applied and the sticky status becomes EKEYRANGE.  n = 0 is a no-op; n > max_batch is EBATCH.
+ * keys/grads may be reused once the stream has passed the call. */
+int ecrm_update(ecrm_ctx *ctx, const uint64_t *keys, const float *grads, uint64_t n, void *hip_stream);
+
+/* Waits for the stream, then returns ECRM_OK, or EKEYRANGE if any batch since the last
+ * ecrm_clear_status (or bind) carried a bad key, or EHIP if the runtime reports an error. */
+int ecrm_status(ecrm_ctx *ctx, void *hip_stream);
+int ecrm_clear_status(ecrm_ctx *ctx, void *hip_stream);
+
+/* Measurement aids (not part of the method).
+ * ecrm_profile(ctx, 1) makes every later ecrm_update record HIP events around its three phases on
+ * the stream it is enqueued on; ecrm_profile_read waits for them, adds up the elapsed time of the
+ * calls recorded since the last read into ms[ECRM_PHASES] and returns the number of calls in
+ * *calls (at most ECRM_PROFILE_MAX_CALLS are kept between reads).
+ * ecrm_batch_stats waits for the stream and reports what the LAST ecrm_update found:
+ *   out[0] = entries updated through the split-chain path (more than ECRM_LONG_RUN updates)
+ *   out[1] = chain pieces those were cut into,  out[2] = items in those entries,
+ *   out[3] = 1 if the batch was rejected for a bad key. */
+enum { ECRM_PHASE_GROUP = 0, ECRM_PHASE_CHAINS = 1, ECRM_PHASE_APPLY = 2, ECRM_PHASES = 3 };
+enum { ECRM_PROFILE_MAX_CALLS = 256, ECRM_LONG_RUN = 256 };
+int ecrm_profile(ecrm_ctx *ctx, int enable);
+int ecrm_profile_read(ecrm_ctx *ctx, double *ms, uint64_t *calls);
+int ecrm_batch_stats(ecrm_ctx *ctx, void *hip_stream, uint64_t *out);
+
+const char *ecrm_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ECRM_H */

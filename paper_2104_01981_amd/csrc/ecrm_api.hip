@@ -1,0 +1,286 @@
+// C ABI of libecrm: argument validation, scratch layout, and the order in which the kernels of one
+// call are enqueued.  No device memory is allocated here; everything lives in caller buffers.
+#include <math.h>
+#include <new>
+#include <string.h>
+
+#include "ecrm_internal.h"
+
+using namespace ecrm;
+
+struct ecrm_ctx {
+    ecrm_config cfg;
+    Geometry geo;
+    int key_bits;
+    uint32_t max_batch, max_slots, max_pieces, max_blocks;
+    size_t scratch_bytes;
+    size_t off_cnt, off_keys[2], off_vals[2], off_hist, off_bintotal, off_long_slot, off_long_meta,
+        off_piece_slot, off_partial, off_long_res;
+    // bound state
+    bool bound, need_init;
+    float *E, *A, *PE, *PA;
+    unsigned long long *load_data, *load_parity;
+    Scratch s;
+    int grid_blocks;          // resident 256-thread blocks for the grid-stride kernels
+    // profiling
+    bool profiling;
+    hipEvent_t ev[ECRM_PROFILE_MAX_CALLS][ECRM_PHASES + 1];
+    bool ev_made;
+    uint32_t ev_calls;
+};
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static void layout(ecrm_ctx *c)
+{
+    const size_t n = c->max_batch, D = c->geo.D;
+    size_t off = sizeof(Header);
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    c->off_cnt = take(2 * (size_t)c->geo.S * sizeof(unsigned long long));
+    for (int i = 0; i < 2; ++i) c->off_keys[i] = take(n * 4);
+    for (int i = 0; i < 2; ++i) c->off_vals[i] = take(n * 4);
+    c->off_hist = take((size_t)kMaxBins * c->max_blocks * 4);
+    c->off_bintotal = take(kMaxBins * 4);
+    c->off_long_slot = take(n * 4);
+    c->off_long_meta = take((size_t)5 * c->max_slots * 4);
+    c->off_piece_slot = take((size_t)c->max_pieces * 4);
+    c->off_partial = take((size_t)c->max_pieces * D * sizeof(double));
+    c->off_long_res = take((size_t)c->max_slots * 2 * D * sizeof(double));
+    c->scratch_bytes = off;
+}
+
+extern "C" {
+
+const char *ecrm_strerror(int code)
+{
+    switch (code) {
+        case ECRM_OK: return "ok";
+        case ECRM_EINVAL: return "invalid argument or configuration";
+        case ECRM_ENOTBOUND: return "no device buffers bound";
+        case ECRM_ESCRATCH: return "scratch buffer missing, misaligned or too small";
+        case ECRM_EBATCH: return "batch larger than max_batch";
+        case ECRM_EKEYRANGE: return "a key was >= rows; that batch was not applied";
+        case ECRM_EHIP: return "HIP runtime error";
+        default: return "unknown error";
+    }
+}
+
+int ecrm_create(const ecrm_config *cfg, ecrm_ctx **out)
+{
+    if (!cfg || !out) return ECRM_EINVAL;
+    *out = nullptr;
+    if (cfg->k < 1 || cfg->k > 64) return ECRM_EINVAL;
+    if (cfg->rows < cfg->k || cfg->rows % cfg->k != 0 || cfg->rows > 0xFFFFFFFFull - 4096) return ECRM_EINVAL;
+    if (cfg->dim < 4 || cfg->dim > 1024 || cfg->dim % 4 != 0) return ECRM_EINVAL;
+    if (cfg->servers < cfg->k + 1 || cfg->servers > 1024) return ECRM_EINVAL;
+    if (cfg->optimizer != ECRM_OPT_ADAGRAD) return ECRM_EINVAL;
+    if (!isfinite(cfg->lr) || !isfinite(cfg->eps) || cfg->eps < 0.0f) return ECRM_EINVAL;
+    if (cfg->max_batch < 1 || cfg->max_batch > (1ull << 31)) return ECRM_EINVAL;
+
+    ecrm_ctx *c = new (std::nothrow) ecrm_ctx;
+    if (!c) return ECRM_EINVAL;
+    memset(c, 0, sizeof(*c));
+    c->cfg = *cfg;
+    c->geo.D = cfg->dim;
+    c->geo.k = cfg->k;
+    c->geo.S = cfg->servers;
+    c->geo.rows = (uint32_t)cfg->rows;
+    c->geo.nc = cfg->dim <= 128 ? 1 : 2;
+    c->geo.ncb = (cfg->dim + c->geo.nc * 128 - 1) / (c->geo.nc * 128);
+    c->geo.lr = cfg->lr;
+    c->geo.eps = cfg->eps;
+    c->key_bits = 1;
+    while (c->key_bits < 32 && (1ull << c->key_bits) < cfg->rows) ++c->key_bits;
+    c->max_batch = (uint32_t)cfg->max_batch;
+    c->max_blocks = (c->max_batch + kSortTile - 1) / kSortTile;
+    c->max_slots = c->max_batch / kLongRun + 1;
+    c->max_pieces = c->max_batch / kPieceMin + c->max_slots + 1;
+    layout(c);
+    *out = c;
+    return ECRM_OK;
+}
+
+void ecrm_destroy(ecrm_ctx *c)
+{
+    if (!c) return;
+    if (c->ev_made)
+        for (int i = 0; i < ECRM_PROFILE_MAX_CALLS; ++i)
+            for (int j = 0; j <= ECRM_PHASES; ++j) (void)hipEventDestroy(c->ev[i][j]);
+    delete c;
+}
+
+size_t ecrm_data_bytes(const ecrm_ctx *c) { return c ? (size_t)c->cfg.rows * c->cfg.dim * 4 : 0; }
+size_t ecrm_parity_bytes(const ecrm_ctx *c) { return c ? (size_t)(c->cfg.rows / c->cfg.k) * c->cfg.dim * 4 : 0; }
+size_t ecrm_scratch_bytes(const ecrm_ctx *c) { return c ? c->scratch_bytes : 0; }
+
+static bool aligned(const void *p, size_t a) { return p && ((uintptr_t)p % a) == 0; }
+
+int ecrm_bind(ecrm_ctx *c, float *E, float *A, float *PE, float *PA, uint64_t *load_data,
+              uint64_t *load_parity, void *scratch, size_t scratch_bytes)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!aligned(E, 16) || !aligned(A, 16) || !aligned(PE, 16) || !aligned(PA, 16)) return ECRM_EINVAL;
+    if (!aligned(load_data, 8) || !aligned(load_parity, 8)) return ECRM_EINVAL;
+    if (!aligned(scratch, 256) || scratch_bytes < c->scratch_bytes) return ECRM_ESCRATCH;
+
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return ECRM_EHIP;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return ECRM_EHIP;
+    (void)per_cu;
+    c->grid_blocks = cus * 8;     // 8 x 256 threads = the 2048 threads a CU can hold
+
+    char *b = (char *)scratch;
+    c->s.hdr = (Header *)b;
+    c->s.cnt = (unsigned long long *)(b + c->off_cnt);
+    for (int i = 0; i < 2; ++i) {
+        c->s.keys[i] = (uint32_t *)(b + c->off_keys[i]);
+        c->s.vals[i] = (uint32_t *)(b + c->off_vals[i]);
+    }
+    c->s.block_hist = (uint32_t *)(b + c->off_hist);
+    c->s.bin_total = (uint32_t *)(b + c->off_bintotal);
+    c->s.long_slot = (uint32_t *)(b + c->off_long_slot);
+    uint32_t *meta = (uint32_t *)(b + c->off_long_meta);
+    c->s.long_head = meta;
+    c->s.long_len = meta + (size_t)c->max_slots;
+    c->s.long_piece = meta + (size_t)2 * c->max_slots;
+    c->s.long_count = meta + (size_t)3 * c->max_slots;
+    c->s.long_base = meta + (size_t)4 * c->max_slots;
+    c->s.piece_slot = (uint32_t *)(b + c->off_piece_slot);
+    c->s.partial = (double *)(b + c->off_partial);
+    c->s.long_res = (double *)(b + c->off_long_res);
+
+    c->E = E; c->A = A; c->PE = PE; c->PA = PA;
+    c->load_data = (unsigned long long *)load_data;
+    c->load_parity = (unsigned long long *)load_parity;
+    c->bound = true;
+    c->need_init = true;      // the first enqueue clears the header on its stream
+    return ECRM_OK;
+}
+
+static int check_launch()
+{
+    return hipGetLastError() == hipSuccess ? ECRM_OK : ECRM_EHIP;
+}
+
+static void init_if_needed(ecrm_ctx *c, hipStream_t st)
+{
+    if (c->need_init) {
+        launch_reset(c->s, c->geo.S, true, st);
+        c->need_init = false;
+    }
+}
+
+int ecrm_encode(ecrm_ctx *c, void *stream)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!c->bound) return ECRM_ENOTBOUND;
+    launch_encode(c->geo, c->E, c->A, c->PE, c->PA, c->grid_blocks, (hipStream_t)stream);
+    return check_launch();
+}
+
+int ecrm_route(ecrm_ctx *c, const uint64_t *keys, uint64_t n, uint64_t *stripe, uint32_t *member,
+               uint32_t *data_srv, uint32_t *parity_srv, void *stream)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!c->bound) return ECRM_ENOTBOUND;
+    if (n == 0) return ECRM_OK;
+    if (!aligned(keys, 8)) return ECRM_EINVAL;
+    init_if_needed(c, (hipStream_t)stream);
+    launch_route(c->s, c->geo, keys, n, stripe, member, data_srv, parity_srv, (hipStream_t)stream);
+    return check_launch();
+}
+
+int ecrm_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uint64_t n, void *stream)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!c->bound) return ECRM_ENOTBOUND;
+    if (n > c->max_batch) return ECRM_EBATCH;
+    if (n == 0) return ECRM_OK;
+    if (!aligned(keys, 8) || !aligned(grads, 16)) return ECRM_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const uint32_t n32 = (uint32_t)n;
+
+    hipEvent_t *ev = nullptr;
+    if (c->profiling && c->ev_calls < ECRM_PROFILE_MAX_CALLS) ev = c->ev[c->ev_calls++];
+
+    launch_reset(c->s, c->geo.S, c->need_init, st);
+    c->need_init = false;
+    if (ev) (void)hipEventRecord(ev[0], st);
+    uint32_t *sk = nullptr, *si = nullptr;
+    launch_sort(c->s, c->geo, keys, n32, c->key_bits, &sk, &si, st);
+    if (ev) (void)hipEventRecord(ev[1], st);
+    launch_chains(c->s, c->geo, c->A, grads, sk, si, n32, c->max_slots, c->max_pieces, c->grid_blocks, st);
+    if (ev) (void)hipEventRecord(ev[2], st);
+    launch_apply(c->s, c->geo, c->E, c->A, c->PE, c->PA, c->load_data, c->load_parity, grads, sk, si, n32,
+                 c->grid_blocks, st);
+    if (ev) (void)hipEventRecord(ev[3], st);
+    return check_launch();
+}
+
+int ecrm_status(ecrm_ctx *c, void *stream)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!c->bound) return ECRM_ENOTBOUND;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return ECRM_EHIP;
+    if (c->need_init) return ECRM_OK;      // nothing was ever enqueued
+    Header h;
+    if (hipMemcpy(&h, c->s.hdr, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return ECRM_EHIP;
+    if (hipGetLastError() != hipSuccess) return ECRM_EHIP;
+    return h.err_sticky ? ECRM_EKEYRANGE : ECRM_OK;
+}
+
+int ecrm_clear_status(ecrm_ctx *c, void *stream)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!c->bound) return ECRM_ENOTBOUND;
+    if (c->need_init) return ECRM_OK;
+    launch_clear_status(c->s, (hipStream_t)stream);
+    return check_launch();
+}
+
+int ecrm_batch_stats(ecrm_ctx *c, void *stream, uint64_t *out)
+{
+    if (!c || !out) return ECRM_EINVAL;
+    if (!c->bound) return ECRM_ENOTBOUND;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return ECRM_EHIP;
+    Header h;
+    memset(&h, 0, sizeof(h));
+    if (!c->need_init && hipMemcpy(&h, c->s.hdr, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return ECRM_EHIP;
+    out[0] = h.n_long;
+    out[1] = h.n_pieces;
+    out[2] = h.n_long_items;
+    out[3] = h.batch_bad;
+    return ECRM_OK;
+}
+
+int ecrm_profile(ecrm_ctx *c, int enable)
+{
+    if (!c) return ECRM_EINVAL;
+    if (enable && !c->ev_made) {
+        for (int i = 0; i < ECRM_PROFILE_MAX_CALLS; ++i)
+            for (int j = 0; j <= ECRM_PHASES; ++j)
+                if (hipEventCreate(&c->ev[i][j]) != hipSuccess) return ECRM_EHIP;
+        c->ev_made = true;
+    }
+    c->profiling = enable != 0;
+    return ECRM_OK;
+}
+
+int ecrm_profile_read(ecrm_ctx *c, double *ms, uint64_t *calls)
+{
+    if (!c || !ms || !calls) return ECRM_EINVAL;
+    for (int j = 0; j < ECRM_PHASES; ++j) ms[j] = 0.0;
+    *calls = c->ev_calls;
+    for (uint32_t i = 0; i < c->ev_calls; ++i) {
+        if (hipEventSynchronize(c->ev[i][ECRM_PHASES]) != hipSuccess) return ECRM_EHIP;
+        for (int j = 0; j < ECRM_PHASES; ++j) {
+            float t = 0.f;
+            if (hipEventElapsedTime(&t, c->ev[i][j], c->ev[i][j + 1]) != hipSuccess) return ECRM_EHIP;
+            ms[j] += (double)t;
+        }
+    }
+    c->ev_calls = 0;
+    return ECRM_OK;
+}
+
+}  // extern "C"

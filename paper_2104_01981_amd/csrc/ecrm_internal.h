@@ -1,0 +1,94 @@
+// Internal declarations shared by the HIP sources of libecrm (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ecrm.h"
+
+namespace ecrm {
+
+// ---- tuning constants -------------------------------------------------------------------------
+constexpr int kWave = 64;            // CDNA wavefront
+constexpr int kGroup = 32;           // lanes that own one row vector: 32 x float4 = 128 floats
+constexpr int kSortThreads = 512;    // 8 waves per sort block
+constexpr int kSortWaves = kSortThreads / kWave;
+constexpr int kSortIpt = 16;         // items per thread
+constexpr int kSortTile = kSortThreads * kSortIpt;   // 8192 items per block
+constexpr int kMaxRadixBits = 9;
+constexpr int kMaxBins = 1 << kMaxRadixBits;
+constexpr uint32_t kLongRun = ECRM_LONG_RUN;  // rows with more updates than this use the split-chain path
+constexpr uint32_t kPieceMin = 128;  // smallest chain piece
+constexpr uint32_t kPieceMaxCount = 1024;     // a chain is cut into at most this many pieces
+constexpr uint32_t kChunk = 8;       // sorted positions owned by one group per grid-stride step
+constexpr uint32_t kNoKey = 0xFFFFFFFFu;
+
+// ---- device-side header at the start of the scratch buffer --------------------------------------
+struct Header {
+    uint32_t err_sticky;   // set once any batch carried a key >= rows
+    uint32_t batch_bad;    // same, for the batch in flight (cleared by reset)
+    uint32_t n_long;       // rows on the split-chain path in this batch
+    uint32_t n_pieces;     // chain pieces in this batch
+    unsigned long long n_long_items;
+    uint32_t pad[58];
+};
+static_assert(sizeof(Header) == 256, "header is one 256-byte block");
+
+struct Scratch {           // device pointers carved out of the caller's scratch buffer
+    Header *hdr;
+    unsigned long long *cnt;       // [2*S] per-batch server counters (data, then parity)
+    uint32_t *keys[2];             // ping-pong sort buffers (row ids)
+    uint32_t *vals[2];             // ping-pong sort buffers (item indices)
+    uint32_t *block_hist;          // [bins][nblocks]
+    uint32_t *bin_total;           // [bins]
+    uint32_t *long_slot;           // [n] slot id, valid at heads of long rows only
+    uint32_t *long_head, *long_len, *long_piece, *long_count, *long_base;   // [max_slots]
+    uint32_t *piece_slot;          // [max_pieces]
+    double *partial;               // [max_pieces][D]
+    double *long_res;              // [max_slots][2][D]: sum of steps, final accumulator
+};
+
+struct Geometry {
+    uint32_t D, k, S;
+    uint32_t rows;         // R (< 2^32)
+    uint32_t nc;           // 128-float chunks a lane holds at once (1 or 2)
+    uint32_t ncb;          // column blocks of nc*128 floats that cover D
+    float lr, eps;
+};
+
+// ---- launchers (each checks nothing: the API layer validates shapes before calling) -------------
+void launch_reset(const Scratch &s, uint32_t S, bool clear_sticky, hipStream_t st);
+void launch_sort(const Scratch &s, const Geometry &g, const uint64_t *keys, uint32_t n, int key_bits,
+                 uint32_t **sorted_keys, uint32_t **sorted_vals, hipStream_t st);
+void launch_chains(const Scratch &s, const Geometry &g, const float *A, const float *grads,
+                   const uint32_t *sk, const uint32_t *si, uint32_t n, uint32_t max_slots,
+                   uint32_t max_pieces, int grid_blocks, hipStream_t st);
+void launch_apply(const Scratch &s, const Geometry &g, float *E, float *A, float *PE, float *PA,
+                  unsigned long long *load_data, unsigned long long *load_parity, const float *grads,
+                  const uint32_t *sk, const uint32_t *si, uint32_t n, int grid_blocks, hipStream_t st);
+void launch_encode(const Geometry &g, const float *E, const float *A, float *PE, float *PA,
+                   int grid_blocks, hipStream_t st);
+void launch_route(const Scratch &s, const Geometry &g, const uint64_t *keys, uint64_t n, uint64_t *stripe,
+                  uint32_t *member, uint32_t *data_srv, uint32_t *parity_srv, hipStream_t st);
+void launch_clear_status(const Scratch &s, hipStream_t st);
+
+// ---- small device helpers ------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & (kWave - 1); }
+
+// One Adagrad step of the printed rule on one parameter, carried in fp64:
+//   G += g^2 ; acc += lr * g / sqrt(G + eps)
+// 1/sqrt comes from the fp32 hardware estimate refined by one Newton step in fp64 (relative error
+// about 1e-13, far below the fp32 rounding of the stored result).
+__device__ __forceinline__ void adagrad_step(double &G, double &acc, float gf, double lr, double eps)
+{
+    const double g = (double)gf;
+    G = fma(g, g, G);
+    const double x = G + eps;
+    double y = (double)__builtin_amdgcn_rsqf((float)x);
+    const double h = 0.5 * x * y;
+    const double t = fma(-h, y, 0.5);
+    y = fma(y, t, y);
+    acc = fma(lr * g, y, acc);
+}
+
+}  // namespace ecrm

@@ -1,0 +1,287 @@
+// Grouping pass of the ECRM update: a stable LSD radix sort of (row id, item index) pairs, so that
+// all updates of an entry -- and, since stripe = row / k, all updates of a stripe -- become
+// contiguous while every entry keeps its arrival order (the per-entry order is what the Adagrad
+// rule of Sec. 3.3.1 depends on).  The first pass also does the integer side of the path: the
+// key-range check, and the per-server load counts of the rotating placement (Sec. 3.2, Sec. 3.6).
+//
+// Three kernels per digit: per-block digit histogram -> per-digit scan over blocks -> stable
+// scatter that ranks items with wave ballots, orders the tile in LDS and writes it out in runs.
+#include "ecrm_internal.h"
+
+namespace ecrm {
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
+{
+    const uint32_t lane = lane_id();
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        uint32_t t = __shfl_up(v, d, kWave);
+        if (lane >= (uint32_t)d) v += t;
+    }
+    return v;
+}
+
+// exclusive scan of one value per thread over a block of kSortThreads; total returned to all
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *s_wave /*[kSortWaves+1]*/,
+                                                    uint32_t &total)
+{
+    const uint32_t lane = lane_id(), wave = threadIdx.x / kWave;
+    const uint32_t incl = wave_incl_scan(v);
+    if (lane == kWave - 1) s_wave[wave] = incl;
+    __syncthreads();
+    uint32_t off = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kSortWaves; ++w) {
+        const uint32_t t = s_wave[w];
+        if ((uint32_t)w < wave) off += t;
+        tot += t;
+    }
+    __syncthreads();
+    total = tot;
+    return off + incl - v;
+}
+
+__global__ void reset_kernel(Header *h, unsigned long long *cnt, uint32_t S, int clear_sticky)
+{
+    const uint32_t t = threadIdx.x;
+    if (t == 0) {
+        h->batch_bad = 0;
+        h->n_long = 0;
+        h->n_pieces = 0;
+        h->n_long_items = 0;
+        if (clear_sticky) h->err_sticky = 0;
+    }
+    for (uint32_t i = t; i < 2 * S; i += blockDim.x) cnt[i] = 0;
+}
+
+__global__ void clear_status_kernel(Header *h)
+{
+    if (threadIdx.x == 0) h->err_sticky = 0;
+}
+
+// ---- histogram ---------------------------------------------------------------------------------
+// FIRST: keys are the caller's u64 row ids; also range check + load accounting.
+template <bool FIRST>
+__global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
+    const void *keys_in, uint32_t n, uint32_t nblocks, int shift, int bits, uint32_t *block_hist,
+    Header *hdr, unsigned long long *cnt, uint32_t rows, uint32_t k, uint32_t S)
+{
+    __shared__ uint32_t s_hist[kMaxBins];
+    __shared__ uint32_t s_cnt[2 * 1024];
+    __shared__ uint32_t s_bad;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t bins = 1u << bits, mask = bins - 1;
+    for (uint32_t i = tid; i < bins; i += kSortThreads) s_hist[i] = 0;
+    if (FIRST) {
+        for (uint32_t i = tid; i < 2 * S; i += kSortThreads) s_cnt[i] = 0;
+        if (tid == 0) s_bad = 0;
+    }
+    __syncthreads();
+    const uint32_t tile0 = blockIdx.x * (uint32_t)kSortTile;
+    const uint32_t wave = tid / kWave, lane = lane_id();
+    bool bad = false;
+#pragma unroll 4
+    for (int r = 0; r < kSortIpt; ++r) {
+        const uint32_t i = tile0 + wave * (kWave * kSortIpt) + r * kWave + lane;
+        if (i < n) {
+            uint32_t key;
+            if (FIRST) {
+                const uint64_t k64 = ((const uint64_t *)keys_in)[i];
+                key = (uint32_t)k64;
+                if (k64 >= (uint64_t)rows) {
+                    bad = true;
+                } else {
+                    const uint32_t g = key / k, j = key - g * k;
+                    atomicAdd(&s_cnt[(g + 1 + j) % S], 1u);       // server of the entry
+                    atomicAdd(&s_cnt[S + g % S], 1u);             // server of its parity
+                }
+            } else {
+                key = ((const uint32_t *)keys_in)[i];
+            }
+            atomicAdd(&s_hist[(key >> shift) & mask], 1u);
+        }
+    }
+    if (FIRST && bad) s_bad = 1;
+    __syncthreads();
+    for (uint32_t b = tid; b < bins; b += kSortThreads) block_hist[(size_t)b * nblocks + blockIdx.x] = s_hist[b];
+    if (FIRST) {
+        for (uint32_t i = tid; i < 2 * S; i += kSortThreads)
+            if (s_cnt[i]) atomicAdd(&cnt[i], (unsigned long long)s_cnt[i]);
+        if (tid == 0 && s_bad) {
+            atomicOr(&hdr->batch_bad, 1u);
+            atomicOr(&hdr->err_sticky, 1u);
+        }
+    }
+}
+
+// ---- per-digit exclusive scan over blocks ----------------------------------------------------------
+__global__ __launch_bounds__(kSortThreads) void sort_scan_kernel(uint32_t *block_hist, uint32_t *bin_total,
+                                                                 uint32_t nblocks)
+{
+    __shared__ uint32_t s_wave[kSortWaves + 1];
+    uint32_t *row = block_hist + (size_t)blockIdx.x * nblocks;
+    uint32_t carry = 0;
+    for (uint32_t base = 0; base < nblocks; base += kSortThreads) {
+        const uint32_t i = base + threadIdx.x;
+        const uint32_t v = i < nblocks ? row[i] : 0;
+        uint32_t total;
+        const uint32_t ex = block_excl_scan(v, s_wave, total);
+        if (i < nblocks) row[i] = carry + ex;
+        carry += total;
+    }
+    if (threadIdx.x == 0) bin_total[blockIdx.x] = carry;
+}
+
+// ---- stable scatter ------------------------------------------------------------------------------
+template <bool FIRST>
+__global__ __launch_bounds__(kSortThreads) void sort_scatter_kernel(
+    const void *keys_in, const uint32_t *vals_in, uint32_t *keys_out, uint32_t *vals_out,
+    const uint32_t *block_hist, const uint32_t *bin_total, uint32_t n, uint32_t nblocks, int shift, int bits)
+{
+    __shared__ uint32_t s_keys[kSortTile];
+    __shared__ uint32_t s_vals[kSortTile];
+    __shared__ uint32_t s_wcnt[kSortWaves][kMaxBins];   // per-wave digit counts, then wave offsets
+    __shared__ uint32_t s_binstart[kMaxBins];           // start of the digit inside the sorted tile
+    __shared__ uint32_t s_gbase[kMaxBins];              // global position of sorted-tile slot 0 of the digit
+    __shared__ uint32_t s_wave[kSortWaves + 1];
+
+    const uint32_t tid = threadIdx.x, wave = tid / kWave, lane = lane_id();
+    const uint32_t bins = 1u << bits, mask = bins - 1;
+    for (uint32_t i = tid; i < kSortWaves * kMaxBins; i += kSortThreads) (&s_wcnt[0][0])[i] = 0;
+    __syncthreads();
+
+    const uint32_t tile0 = blockIdx.x * (uint32_t)kSortTile;
+    uint32_t key[kSortIpt], val[kSortIpt], rank[kSortIpt];
+#pragma unroll
+    for (int r = 0; r < kSortIpt; ++r) {
+        const uint32_t i = tile0 + wave * (kWave * kSortIpt) + r * kWave + lane;
+        key[r] = 0;
+        val[r] = 0;
+        if (i < n) {
+            if (FIRST) {
+                key[r] = (uint32_t)((const uint64_t *)keys_in)[i];
+                val[r] = i;
+            } else {
+                key[r] = ((const uint32_t *)keys_in)[i];
+                val[r] = vals_in[i];
+            }
+        }
+    }
+
+    // rank inside the wave: items are ordered (r, lane); equal digits are matched with ballots
+    const unsigned long long lt = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int r = 0; r < kSortIpt; ++r) {
+        const uint32_t i = tile0 + wave * (kWave * kSortIpt) + r * kWave + lane;
+        const bool valid = i < n;
+        const uint32_t digit = (key[r] >> shift) & mask;
+        unsigned long long peers = __ballot(valid);
+        for (int b = 0; b < bits; ++b) {
+            const bool bit = (digit >> b) & 1u;
+            const unsigned long long bal = __ballot(bit);
+            peers &= bit ? bal : ~bal;
+        }
+        const uint32_t below = __popcll(peers & lt);
+        const uint32_t old = s_wcnt[wave][digit];
+        __builtin_amdgcn_wave_barrier();
+        if (valid && below == 0) s_wcnt[wave][digit] = old + (uint32_t)__popcll(peers);
+        __builtin_amdgcn_wave_barrier();
+        rank[r] = old + below;
+    }
+    __syncthreads();
+
+    // per digit: exclusive scan over the waves, total of the block
+    uint32_t my_total = 0;
+    if (tid < bins) {
+        uint32_t run = 0;
+#pragma unroll
+        for (int w = 0; w < kSortWaves; ++w) {
+            const uint32_t t = s_wcnt[w][tid];
+            s_wcnt[w][tid] = run;
+            run += t;
+        }
+        my_total = run;
+    }
+    uint32_t dummy;
+    const uint32_t binstart = block_excl_scan(my_total, s_wave, dummy);
+    const uint32_t gtot = tid < bins ? bin_total[tid] : 0;
+    const uint32_t gstart = block_excl_scan(gtot, s_wave, dummy);
+    if (tid < bins) {
+        s_binstart[tid] = binstart;
+        s_gbase[tid] = gstart + block_hist[(size_t)tid * nblocks + blockIdx.x] - binstart;
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int r = 0; r < kSortIpt; ++r) {
+        const uint32_t i = tile0 + wave * (kWave * kSortIpt) + r * kWave + lane;
+        if (i < n) {
+            const uint32_t digit = (key[r] >> shift) & mask;
+            const uint32_t pos = s_binstart[digit] + s_wcnt[wave][digit] + rank[r];
+            s_keys[pos] = key[r];
+            s_vals[pos] = val[r];
+        }
+    }
+    __syncthreads();
+
+    const uint32_t count = min((uint32_t)kSortTile, n - tile0);
+    for (uint32_t i = tid; i < count; i += kSortThreads) {
+        const uint32_t kk = s_keys[i];
+        const uint32_t gpos = s_gbase[(kk >> shift) & mask] + i;
+        keys_out[gpos] = kk;
+        vals_out[gpos] = s_vals[i];
+    }
+}
+
+// ---- host side -------------------------------------------------------------------------------------
+void launch_reset(const Scratch &s, uint32_t S, bool clear_sticky, hipStream_t st)
+{
+    hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, st, s.hdr, s.cnt, S, clear_sticky ? 1 : 0);
+}
+
+void launch_clear_status(const Scratch &s, hipStream_t st)
+{
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, st, s.hdr);
+}
+
+void launch_sort(const Scratch &s, const Geometry &g, const uint64_t *keys, uint32_t n, int key_bits,
+                 uint32_t **sorted_keys, uint32_t **sorted_vals, hipStream_t st)
+{
+    const uint32_t nblocks = (n + kSortTile - 1) / kSortTile;
+    int passes = (key_bits + kMaxRadixBits - 1) / kMaxRadixBits;
+    if (passes < 1) passes = 1;
+    int shift = 0, cur = 0;
+    for (int p = 0; p < passes; ++p) {
+        // spread the bits as evenly as possible, wider digits first
+        const int left = key_bits - shift;
+        int bits = (left + (passes - p) - 1) / (passes - p);
+        if (bits < 1) bits = 1;
+        const uint32_t bins = 1u << bits;
+        if (p == 0) {
+            hipLaunchKernelGGL(sort_hist_kernel<true>, dim3(nblocks), dim3(kSortThreads), 0, st,
+                               (const void *)keys, n, nblocks, shift, bits, s.block_hist, s.hdr, s.cnt,
+                               g.rows, g.k, g.S);
+            hipLaunchKernelGGL(sort_scan_kernel, dim3(bins), dim3(kSortThreads), 0, st, s.block_hist,
+                               s.bin_total, nblocks);
+            hipLaunchKernelGGL(sort_scatter_kernel<true>, dim3(nblocks), dim3(kSortThreads), 0, st,
+                               (const void *)keys, (const uint32_t *)nullptr, s.keys[0], s.vals[0],
+                               s.block_hist, s.bin_total, n, nblocks, shift, bits);
+            cur = 0;
+        } else {
+            hipLaunchKernelGGL(sort_hist_kernel<false>, dim3(nblocks), dim3(kSortThreads), 0, st,
+                               (const void *)s.keys[cur], n, nblocks, shift, bits, s.block_hist, s.hdr,
+                               s.cnt, g.rows, g.k, g.S);
+            hipLaunchKernelGGL(sort_scan_kernel, dim3(bins), dim3(kSortThreads), 0, st, s.block_hist,
+                               s.bin_total, nblocks);
+            hipLaunchKernelGGL(sort_scatter_kernel<false>, dim3(nblocks), dim3(kSortThreads), 0, st,
+                               (const void *)s.keys[cur], s.vals[cur], s.keys[cur ^ 1], s.vals[cur ^ 1],
+                               s.block_hist, s.bin_total, n, nblocks, shift, bits);
+            cur ^= 1;
+        }
+        shift += bits;
+    }
+    *sorted_keys = s.keys[cur];
+    *sorted_vals = s.vals[cur];
+}
+
+}  // namespace ecrm

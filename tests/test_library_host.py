@@ -1,0 +1,82 @@
+"""Host-side checks of libecrm that need no GPU: the library loads, exports every symbol the
+header declares, validates configurations, and reports the sizes the paper's overhead formula
+gives (Sec. 2.4 / 3.1: a (k+r)/k code with r = 1)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2104_01981_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.library_path()):
+        from paper_2104_01981_amd import build
+        build.build()
+    return binding.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "ecrm.h")).read()
+    declared = set(re.findall(r"\b(ecrm_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.SYMBOLS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def _create(lib, **kw):
+    base = dict(rows=1 << 14, dim=128, k=4, servers=5, optimizer=0, lr=0.01, eps=1e-8, max_batch=1 << 16)
+    base.update(kw)
+    cfg = binding.EcrmConfig(**base)
+    ctx = C.c_void_p(0)
+    rc = lib.ecrm_create(C.byref(cfg), C.byref(ctx))
+    return rc, ctx
+
+
+@pytest.mark.parametrize("kw", [dict(rows=10), dict(rows=3), dict(dim=130), dict(dim=0), dict(dim=2048),
+                                dict(k=0), dict(k=65, rows=65 * 4, servers=70), dict(servers=4),
+                                dict(servers=2000), dict(optimizer=1), dict(lr=float("nan")), dict(eps=-1.0),
+                                dict(max_batch=0), dict(max_batch=(1 << 31) + 1), dict(rows=1 << 32)])
+def test_create_rejects_bad_config(lib, kw):
+    rc, ctx = _create(lib, **kw)
+    assert rc == binding.ECRM_EINVAL and not ctx.value
+
+
+@pytest.mark.parametrize("k,R,D", [(2, 1 << 12, 128), (4, 1 << 12, 128), (10, 10 * 400, 256)])
+def test_memory_overhead_is_k_plus_1_over_k(lib, k, R, D):
+    rc, ctx = _create(lib, rows=R, dim=D, k=k, servers=k + 1)
+    assert rc == 0
+    data, par = lib.ecrm_data_bytes(ctx), lib.ecrm_parity_bytes(ctx)
+    assert data == R * D * 4 and par * k == data          # 50 %, 25 %, 10 % for k = 2, 4, 10
+    assert lib.ecrm_scratch_bytes(ctx) % 256 == 0 and lib.ecrm_scratch_bytes(ctx) > 0
+    lib.ecrm_destroy(ctx)
+
+
+def test_unbound_context_refuses_work(lib):
+    rc, ctx = _create(lib)
+    assert rc == 0
+    assert lib.ecrm_encode(ctx, None) == binding.ECRM_ENOTBOUND
+    assert lib.ecrm_update(ctx, None, None, 1, None) == binding.ECRM_ENOTBOUND
+    assert lib.ecrm_status(ctx, None) == binding.ECRM_ENOTBOUND
+    lib.ecrm_destroy(ctx)
+    lib.ecrm_destroy(None)
+
+
+def test_strerror(lib):
+    for code in range(-6, 1):
+        assert len(lib.ecrm_strerror(code)) > 1
+    assert b"unknown" in lib.ecrm_strerror(-99)
+
+
+def test_scratch_grows_with_batch(lib):
+    sizes = []
+    for mb in (1 << 10, 1 << 16, 1 << 20):
+        rc, ctx = _create(lib, max_batch=mb)
+        sizes.append(lib.ecrm_scratch_bytes(ctx))
+        lib.ecrm_destroy(ctx)
+    assert sizes[0] < sizes[1] < sizes[2]
+    assert sizes[2] < (1 << 20) * 64          # well under 64 B per item
