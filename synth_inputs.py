@@ -136,66 +136,90 @@ def table(seed: int, tag: int, R: int, D: int, device="cpu") -> torch.Tensor:
 
 
 # ----------------------------------------------------------------------------------------------
-# keys
+# keys (torch int64 tensors on `device`; the *_keys wrappers return host u64 arrays)
 # ----------------------------------------------------------------------------------------------
 
-def _hash_np(seed: int, tag: int, start: int, count: int) -> np.ndarray:
-    idx = torch.arange(start, start + count, dtype=torch.int64)
-    return hash_tensor(seed, tag, idx).numpy().view(np.uint64)
-
-
-def uniform_keys(seed: int, start: int, count: int, R: int) -> np.ndarray:
-    """Uniform row ids in [0, R): (hash >> 1) mod R, as u64."""
-    h = _hash_np(seed, TAG_KEY_UNIFORM, start, count)
-    return (h >> np.uint64(1)) % np.uint64(R)
+def uniform_keys_t(seed: int, start: int, count: int, R: int, device="cpu") -> torch.Tensor:
+    """Uniform row ids in [0, R): (hash >> 1) mod R."""
+    idx = torch.arange(start, start + count, dtype=torch.int64, device=device)
+    return _lsr(hash_tensor(seed, TAG_KEY_UNIFORM, idx), 1) % R
 
 
 _zipf_cache: dict = {}
 
 
 def zipf_cdf(n_ranks: int, theta: float) -> np.ndarray:
-    """Normalised fp64 prefix table of the weights r^-theta, r = 1..n_ranks."""
+    """Normalised fp64 prefix table of the weights r^-theta, r = 1..n_ranks (always summed on the
+    host, sequentially, so that every device sees the same table)."""
     key = (n_ranks, theta)
     if key not in _zipf_cache:
         w = np.arange(1, n_ranks + 1, dtype=np.float64) ** (-theta)
         c = np.cumsum(w)
         c /= c[-1]
         _zipf_cache.clear()
-        _zipf_cache[key] = c
-    return _zipf_cache[key]
+        _zipf_cache[key] = {"cpu": torch.from_numpy(c)}
+    return _zipf_cache[key]["cpu"].numpy()
 
 
-def _scatter_ranks(seed: int, rank: np.ndarray, n_ranks: int, R: int) -> np.ndarray:
+def _zipf_cdf_t(n_ranks: int, theta: float, device) -> torch.Tensor:
+    zipf_cdf(n_ranks, theta)
+    slot = _zipf_cache[(n_ranks, theta)]
+    dev = str(torch.device(device))
+    if dev not in slot:
+        slot[dev] = slot["cpu"].to(device)
+    return slot[dev]
+
+
+def _scatter_ranks_t(seed: int, rank: torch.Tensor, n_ranks: int, R: int) -> torch.Tensor:
     """Injective map rank -> row: an odd-multiplier bijection of [0, n_ranks) (n_ranks a power of
     two), spread over R >= n_ranks rows by a per-rank hashed offset inside R // n_ranks."""
     assert n_ranks & (n_ranks - 1) == 0 and R >= n_ranks and R % n_ranks == 0
-    odd = np.uint64(0x9E3779B1)
-    perm = (rank.astype(np.uint64) * odd) & np.uint64(n_ranks - 1)
+    perm = (rank * 0x9E3779B1) & (n_ranks - 1)
     spread = R // n_ranks
     if spread == 1:
         return perm
-    hr = hash_tensor(seed, TAG_SCATTER, torch.from_numpy(rank.astype(np.int64))).numpy().view(np.uint64)
-    return perm * np.uint64(spread) + (hr >> np.uint64(1)) % np.uint64(spread)
+    return perm * spread + _lsr(hash_tensor(seed, TAG_SCATTER, rank), 1) % spread
 
 
-def zipf_keys(seed: int, start: int, count: int, R: int, n_ranks: int, theta: float = 0.99) -> np.ndarray:
-    """Row ids whose popularity rank follows Zipf(theta) over n_ranks ranks (exact inverse CDF)."""
-    h = _hash_np(seed, TAG_KEY_ZIPF, start, count)
-    u = (h >> np.uint64(11)).astype(np.float64) * (2.0 ** -53)
-    cdf = zipf_cdf(n_ranks, theta)
-    rank = np.searchsorted(cdf, u, side="right")
-    rank = np.minimum(rank, n_ranks - 1)
-    return _scatter_ranks(seed, rank, n_ranks, R)
+def _scatter_ranks(seed: int, rank: np.ndarray, n_ranks: int, R: int) -> np.ndarray:
+    r = torch.from_numpy(np.asarray(rank, dtype=np.int64))
+    return _scatter_ranks_t(seed, r, n_ranks, R).numpy().view(np.uint64)
 
 
-def mixed_keys(seed: int, start: int, count: int, R: int, n_ranks: int, theta: float = 0.99) -> np.ndarray:
+def zipf_keys_t(seed: int, start: int, count: int, R: int, n_ranks: int, theta: float = 0.99,
+                device="cpu") -> torch.Tensor:
+    """Row ids whose popularity rank follows Zipf(theta) over n_ranks ranks (exact inverse CDF:
+    binary search of a 53-bit uniform in the prefix table)."""
+    idx = torch.arange(start, start + count, dtype=torch.int64, device=device)
+    u = _lsr(hash_tensor(seed, TAG_KEY_ZIPF, idx), 11).to(torch.float64) * (2.0 ** -53)
+    rank = torch.searchsorted(_zipf_cdf_t(n_ranks, theta, device), u, right=True)
+    rank = torch.clamp(rank, max=n_ranks - 1)
+    return _scatter_ranks_t(seed, rank, n_ranks, R)
+
+
+def mixed_keys_t(seed: int, start: int, count: int, R: int, n_ranks: int, theta: float = 0.99,
+                 device="cpu") -> torch.Tensor:
     """Even item indices uniform, odd item indices Zipf (the interleaved HBM-scale stream)."""
     assert start % 2 == 0
-    ku = uniform_keys(seed, start, count, R)
-    kz = zipf_keys(seed, start, count, R, n_ranks, theta)
-    out = ku.copy()
-    out[1::2] = kz[1::2]
+    out = uniform_keys_t(seed, start, count, R, device)
+    out[1::2] = zipf_keys_t(seed, start, count, R, n_ranks, theta, device)[1::2]
     return out
+
+
+def _host(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint64)
+
+
+def uniform_keys(seed, start, count, R):
+    return _host(uniform_keys_t(seed, start, count, R))
+
+
+def zipf_keys(seed, start, count, R, n_ranks, theta=0.99):
+    return _host(zipf_keys_t(seed, start, count, R, n_ranks, theta))
+
+
+def mixed_keys(seed, start, count, R, n_ranks, theta=0.99):
+    return _host(mixed_keys_t(seed, start, count, R, n_ranks, theta))
 
 
 # ----------------------------------------------------------------------------------------------
@@ -218,18 +242,21 @@ DEFAULT_LR = 0.01
 DEFAULT_EPS = 1e-8
 
 
-def workload_keys(name: str, batch: int = 0, scale_shift: int = 0) -> np.ndarray:
-    """Keys of one batch of a named workload.  ``scale_shift`` halves n, R and the rank count that
-    many times (same recipe, smaller: for CPU-side tests of the generators and of the kernels'
-    skew handling)."""
+def workload_keys_t(name: str, batch: int = 0, scale_shift: int = 0, device="cpu") -> torch.Tensor:
+    """Keys (int64 tensor on `device`) of one batch of a named workload.  ``scale_shift`` halves n,
+    R and the rank count that many times (same recipe, smaller)."""
     w = WORKLOADS[name]
     n = w["n"] >> scale_shift
     R = w["R"] >> scale_shift
     per = n // w["batches"]
     start = batch * per
     if w["kind"] == "uniform":
-        return uniform_keys(w["seed"], start, per, R)
+        return uniform_keys_t(w["seed"], start, per, R, device)
     nr = w["n_ranks"] >> scale_shift
     if w["kind"] == "zipf":
-        return zipf_keys(w["seed"], start, per, R, nr)
-    return mixed_keys(w["seed"], start, per, R, nr)
+        return zipf_keys_t(w["seed"], start, per, R, nr, device=device)
+    return mixed_keys_t(w["seed"], start, per, R, nr, device=device)
+
+
+def workload_keys(name: str, batch: int = 0, scale_shift: int = 0) -> np.ndarray:
+    return _host(workload_keys_t(name, batch, scale_shift))
