@@ -132,7 +132,7 @@ def main():
         "config": {"workload": f"{args.workload}" + (f">>{sh}" if sh else ""), "items_per_step": per,
                    "rows": R, "dim": D, "k": k, "servers": S, "storage": "f32", "optimizer": "adagrad",
                    "keys": w["kind"], "batches_resident": nb},
-        "roofline": {"bound": "hbm", "kernel": "apply_stripes_kernel<1>", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "apply_stripes_kernel_d128", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "algorithmic_bytes_per_launch": apply_bytes, "avg_launch_ms": apply_ms},
         "phases_ms_per_step": {"group": ms[0] / calls, "chains": ms[1] / calls, "apply": apply_ms},

@@ -21,7 +21,8 @@ struct ecrm_ctx {
     float *E, *A, *PE, *PA;
     unsigned long long *load_data, *load_parity;
     Scratch s;
-    int grid_blocks;          // resident 256-thread blocks for the grid-stride kernels
+    int grid_blocks;          // 8 blocks of 256 threads per CU, for the streaming kernels
+    int cus;
     // profiling
     bool profiling;
     hipEvent_t ev[ECRM_PROFILE_MAX_CALLS][ECRM_PHASES + 1];
@@ -127,6 +128,7 @@ int ecrm_bind(ecrm_ctx *c, float *E, float *A, float *PE, float *PA, uint64_t *l
     if (hipGetDevice(&dev) != hipSuccess) return ECRM_EHIP;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return ECRM_EHIP;
     (void)per_cu;
+    c->cus = cus;
     c->grid_blocks = cus * 8;     // 8 x 256 threads = the 2048 threads a CU can hold
 
     char *b = (char *)scratch;
@@ -209,10 +211,10 @@ int ecrm_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uint64_t 
     uint32_t *sk = nullptr, *si = nullptr;
     launch_sort(c->s, c->geo, keys, n32, c->key_bits, &sk, &si, st);
     if (ev) (void)hipEventRecord(ev[1], st);
-    launch_chains(c->s, c->geo, c->A, grads, sk, si, n32, c->max_slots, c->max_pieces, c->grid_blocks, st);
+    launch_chains(c->s, c->geo, c->A, grads, sk, si, n32, c->max_slots, c->max_pieces, c->cus, st);
     if (ev) (void)hipEventRecord(ev[2], st);
     launch_apply(c->s, c->geo, c->E, c->A, c->PE, c->PA, c->load_data, c->load_parity, grads, sk, si, n32,
-                 c->grid_blocks, st);
+                 c->cus, st);
     if (ev) (void)hipEventRecord(ev[3], st);
     return check_launch();
 }

@@ -10,7 +10,7 @@ namespace ecrm {
 
 // ---- tuning constants -------------------------------------------------------------------------
 constexpr int kWave = 64;            // CDNA wavefront
-constexpr int kGroup = 32;           // lanes that own one row vector: 32 x float4 = 128 floats
+
 constexpr int kSortThreads = 512;    // 8 waves per sort block
 constexpr int kSortWaves = kSortThreads / kWave;
 constexpr int kSortIpt = 16;         // items per thread
@@ -20,7 +20,7 @@ constexpr int kMaxBins = 1 << kMaxRadixBits;
 constexpr uint32_t kLongRun = ECRM_LONG_RUN;  // rows with more updates than this use the split-chain path
 constexpr uint32_t kPieceMin = 128;  // smallest chain piece
 constexpr uint32_t kPieceMaxCount = 1024;     // a chain is cut into at most this many pieces
-constexpr uint32_t kChunk = 8;       // sorted positions owned by one group per grid-stride step
+constexpr uint32_t kChunk = 32;      // sorted positions whose stripes one wave owns per grid-stride step
 constexpr uint32_t kNoKey = 0xFFFFFFFFu;
 
 // ---- device-side header at the start of the scratch buffer --------------------------------------
@@ -62,10 +62,10 @@ void launch_sort(const Scratch &s, const Geometry &g, const uint64_t *keys, uint
                  uint32_t **sorted_keys, uint32_t **sorted_vals, hipStream_t st);
 void launch_chains(const Scratch &s, const Geometry &g, const float *A, const float *grads,
                    const uint32_t *sk, const uint32_t *si, uint32_t n, uint32_t max_slots,
-                   uint32_t max_pieces, int grid_blocks, hipStream_t st);
+                   uint32_t max_pieces, int cus, hipStream_t st);
 void launch_apply(const Scratch &s, const Geometry &g, float *E, float *A, float *PE, float *PA,
                   unsigned long long *load_data, unsigned long long *load_parity, const float *grads,
-                  const uint32_t *sk, const uint32_t *si, uint32_t n, int grid_blocks, hipStream_t st);
+                  const uint32_t *sk, const uint32_t *si, uint32_t n, int cus, hipStream_t st);
 void launch_encode(const Geometry &g, const float *E, const float *A, float *PE, float *PA,
                    int grid_blocks, hipStream_t st);
 void launch_route(const Scratch &s, const Geometry &g, const uint64_t *keys, uint64_t n, uint64_t *stripe,

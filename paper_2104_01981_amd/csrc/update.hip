@@ -1,83 +1,91 @@
 // The floating-point side of the ECRM update, on items already grouped by row (sort.hip):
 //
-//   apply_stripes   one 32-lane group per stripe: for each touched entry walk its updates in arrival
-//                   order (Adagrad, Sec. 3.3.1), store the entry and its accumulator once, and add
-//                   the entry's total difference in value and in accumulator to the stripe's parity
-//                   rows (difference propagation, Sec. 3.3.2), which are read and written once.
-//                   The differences of one call telescope, so adding their sum is the same as adding
-//                   them one by one.
+//   apply_stripes   for each touched entry walk its updates in arrival order (Adagrad, Sec. 3.3.1),
+//                   store the entry and its accumulator once, and add the entry's total difference in
+//                   value and in accumulator to the stripe's parity rows (difference propagation,
+//                   Sec. 3.3.2), which are read and written once per call.  The differences of one
+//                   call telescope, so adding their sum is the same as adding them one by one.
 //
 //   chains          entries that receive more than kLongRun updates in one call (the head of a
-//                   skewed key distribution) are not walked by one group.  For a run g_1..g_m on one
-//                   parameter, G_t = G_0 + sum_{s<=t} g_s^2 is a prefix sum and the entry moves by
-//                   -lr * sum_t g_t / sqrt(G_t + eps); so the run is cut into pieces: (1) each piece
-//                   sums its g^2, (2) a scan over the pieces gives every piece its starting
+//                   skewed key distribution) are not walked by one wavefront.  For a run g_1..g_m on
+//                   one parameter, G_t = G_0 + sum_{s<=t} g_s^2 is a prefix sum and the entry moves
+//                   by -lr * sum_t g_t / sqrt(G_t + eps); so the run is cut into pieces: (1) each
+//                   piece sums its g^2, (2) a scan over the pieces gives every piece its starting
 //                   accumulator, (3) each piece sums its steps, (4) the pieces' sums are added in
 //                   order.  apply_stripes then takes the entry's totals from there.
 //
-// A "group" is half a wavefront: 32 lanes x float4 = one 128-float slice of a row, so one load
-// instruction of a group moves 512 contiguous bytes.  All chain arithmetic is carried in fp64.
+// One wavefront works on one row at a time: 64 lanes x float2 = a 128-float slice, so a load
+// instruction of the wave moves 512 contiguous bytes from a wave-uniform (scalar) row address, and
+// all control flow is wave-uniform.  All chain arithmetic is carried in fp64.
 #include "ecrm_internal.h"
 
 namespace ecrm {
 
-struct Cols {                 // which floats of a row this lane holds in column block cb
-    uint32_t col[2];
-    bool on[2];
-};
+// A row (or the part of it that starts at column block cb) as a bounds-checked buffer resource:
+// the base is wave-uniform and lives in scalar registers, each lane adds only its 32-bit byte
+// offset, loads past the end of the row return 0 and stores past it are dropped -- so rows shorter
+// than the 128 floats a wave spans need no lane predicates.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr int kRsrcFlags = 0x00020000;     // raw 32-bit data format (gfx9 family)
 
-template <int NC>
-__device__ __forceinline__ Cols lane_cols(uint32_t D, uint32_t cb)
+__device__ __forceinline__ rsrc_t row_f32(const float *table, uint32_t row, uint32_t D, uint32_t col0)
 {
-    Cols c;
-    const uint32_t gl = threadIdx.x & (kGroup - 1);
-#pragma unroll
-    for (int i = 0; i < NC; ++i) {
-        c.col[i] = (cb * NC + i) * 128u + gl * 4u;
-        c.on[i] = c.col[i] < D;
-    }
-    return c;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(table + (size_t)row * D + col0), 0,
+                                             (int)((D - col0) * 4u), kRsrcFlags);
 }
-
-__device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
-__device__ __forceinline__ void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
-__device__ __forceinline__ double2 ldd2(const double *p) { return *reinterpret_cast<const double2 *>(p); }
-__device__ __forceinline__ void std2(double *p, double2 v) { *reinterpret_cast<double2 *>(p) = v; }
-
-struct D4 { double v[4]; };
-
-__device__ __forceinline__ D4 ldd4(const double *p)
+__device__ __forceinline__ rsrc_t row_f64(const double *table, size_t row, uint32_t D, uint32_t col0)
 {
-    const double2 a = ldd2(p), b = ldd2(p + 2);
-    return D4{{a.x, a.y, b.x, b.y}};
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<double *>(table + row * D + col0), 0,
+                                             (int)((D - col0) * 8u), kRsrcFlags);
 }
-__device__ __forceinline__ void std4(double *p, const D4 &d)
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+// lane's float2 of 128-float slice i of the row
+__device__ __forceinline__ float2 ld2(rsrc_t r, int i)
 {
-    std2(p, double2{d.v[0], d.v[1]});
-    std2(p + 2, double2{d.v[2], d.v[3]});
+    return __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(r, (int)(lane_id() * 8u + i * 512u), 0, 0));
 }
-__device__ __forceinline__ D4 widen4(float4 f) { return D4{{(double)f.x, (double)f.y, (double)f.z, (double)f.w}}; }
-__device__ __forceinline__ float4 narrow4(const D4 &d)
+__device__ __forceinline__ void st2(rsrc_t r, int i, float2 v)
 {
-    return float4{(float)d.v[0], (float)d.v[1], (float)d.v[2], (float)d.v[3]};
-}
-__device__ __forceinline__ void step4(D4 &G, D4 &acc, float4 g, double lr, double eps)
-{
-    adagrad_step(G.v[0], acc.v[0], g.x, lr, eps);
-    adagrad_step(G.v[1], acc.v[1], g.y, lr, eps);
-    adagrad_step(G.v[2], acc.v[2], g.z, lr, eps);
-    adagrad_step(G.v[3], acc.v[3], g.w, lr, eps);
-}
-__device__ __forceinline__ void sumsq4(D4 &s, float4 g)
-{
-    s.v[0] = fma((double)g.x, (double)g.x, s.v[0]);
-    s.v[1] = fma((double)g.y, (double)g.y, s.v[1]);
-    s.v[2] = fma((double)g.z, (double)g.z, s.v[2]);
-    s.v[3] = fma((double)g.w, (double)g.w, s.v[3]);
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, v), r, (int)(lane_id() * 8u + i * 512u), 0, 0);
 }
 
-__device__ __forceinline__ uint32_t group_id() { return (blockIdx.x * blockDim.x + threadIdx.x) / kGroup; }
-__device__ __forceinline__ uint32_t group_count() { return (gridDim.x * blockDim.x) / kGroup; }
+struct D2 { double x, y; };
+__device__ __forceinline__ D2 ldd2(rsrc_t r, int i)
+{
+    const double2 v = __builtin_bit_cast(double2, __builtin_amdgcn_raw_buffer_load_b128(r, (int)(lane_id() * 16u + i * 1024u), 0, 0));
+    return D2{v.x, v.y};
+}
+__device__ __forceinline__ void std2(rsrc_t r, int i, D2 d)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, double2{d.x, d.y}), r, (int)(lane_id() * 16u + i * 1024u), 0, 0);
+}
+__device__ __forceinline__ D2 widen2(float2 f) { return D2{(double)f.x, (double)f.y}; }
+__device__ __forceinline__ float2 narrow2(D2 d) { return float2{(float)d.x, (float)d.y}; }
+__device__ __forceinline__ void step2(D2 &G, D2 &acc, float2 g, double lr, double eps)
+{
+    adagrad_step(G.x, acc.x, g.x, lr, eps);
+    adagrad_step(G.y, acc.y, g.y, lr, eps);
+}
+__device__ __forceinline__ void sumsq2(D2 &s, float2 g)
+{
+    s.x = fma((double)g.x, (double)g.x, s.x);
+    s.y = fma((double)g.y, (double)g.y, s.y);
+}
+
+__device__ __forceinline__ uint32_t wave_id() { return (blockIdx.x * blockDim.x + threadIdx.x) / kWave; }
+__device__ __forceinline__ uint32_t wave_count() { return (gridDim.x * blockDim.x) / kWave; }
+// value of v in lane j, j wave-uniform: the result is wave-uniform (scalar)
+__device__ __forceinline__ uint32_t from_lane(uint32_t v, uint32_t j)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)j);
+}
+__device__ __forceinline__ uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ uint32_t lowest_bit(unsigned long long m) { return (uint32_t)__builtin_ctzll(m); }
+__device__ __forceinline__ unsigned long long bits_below(uint32_t j)      // j in 0..64
+{
+    return j >= 64 ? ~0ull : ((1ull << j) - 1ull);
+}
 
 // ================================================================================================
 // split-chain path
@@ -138,6 +146,8 @@ __global__ __launch_bounds__(256) void long_plan_kernel(const uint32_t *sk, uint
 // Phase 1 (STEPS == false): partial[piece] = sum of g^2 over the piece.
 // Phase 3 (STEPS == true):  partial[piece] holds the piece's starting accumulator on entry and the
 //                           sum of its steps lr * g_t / sqrt(G_t + eps) on exit.
+// One wave per piece; the item indices of 64 positions are fetched with one coalesced load and
+// handed out lane by lane, and U gradient rows are in flight at a time.
 template <int NC, bool STEPS>
 __global__ __launch_bounds__(256) void long_piece_kernel(const uint32_t *si, const float *grads, Header *hdr,
                                                          const uint32_t *long_head, const uint32_t *long_len,
@@ -147,56 +157,60 @@ __global__ __launch_bounds__(256) void long_piece_kernel(const uint32_t *si, con
 {
     if (hdr->batch_bad) return;
     const uint32_t np = min(hdr->n_pieces, max_pieces);
-    const uint32_t D = geo.D;
+    const uint32_t D = geo.D, lane = lane_id();
     const double lr = (double)geo.lr, eps = (double)geo.eps;
-    constexpr int U = 8;
-    for (uint32_t pc = group_id(); pc < np; pc += group_count()) {
-        const uint32_t slot = piece_slot[pc];
-        const uint32_t j = pc - long_base[slot];
-        const uint32_t head = long_head[slot], L = long_len[slot], C = long_piece[slot];
+    constexpr int U = 16;
+    for (uint32_t pc = wave_id(); pc < np; pc += wave_count()) {
+        const uint32_t slot = uniform(piece_slot[pc]);
+        const uint32_t j = pc - uniform(long_base[slot]);
+        const uint32_t head = uniform(long_head[slot]), L = uniform(long_len[slot]), C = uniform(long_piece[slot]);
         const uint32_t start = head + j * C;
         const uint32_t end = min(start + C, head + L);
         for (uint32_t cb = 0; cb < geo.ncb; ++cb) {
-            const Cols c = lane_cols<NC>(D, cb);
-            D4 G[NC], acc[NC];
+            const uint32_t col0 = cb * NC * 128u;
+            const rsrc_t part = row_f64(partial, pc, D, col0);
+            D2 G[NC], acc[NC];
 #pragma unroll
             for (int i = 0; i < NC; ++i) {
-                acc[i] = D4{{0, 0, 0, 0}};
-                G[i] = D4{{0, 0, 0, 0}};
-                if (STEPS && c.on[i]) G[i] = ldd4(partial + (size_t)pc * D + c.col[i]);
+                acc[i] = D2{0, 0};
+                G[i] = STEPS ? ldd2(part, i) : D2{0, 0};
             }
-            for (uint32_t cur = start; cur < end; cur += U) {
-                float4 g[U][NC];
+            uint32_t widx = start + lane < end ? si[start + lane] : 0u;
+            for (uint32_t base = start; base < end; base += kWave) {
+                const uint32_t cnt = min((uint32_t)kWave, end - base);
+                const uint32_t cur_idx = widx;
+                if (base + kWave < end)            // next window in flight while this one is consumed
+                    widx = base + kWave + lane < end ? si[base + kWave + lane] : 0u;
+                for (uint32_t u0 = 0; u0 < cnt; u0 += U) {
+                    float2 g[U][NC];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const bool live = cur + u < end;
-                    const uint32_t idx = live ? si[cur + u] : 0;
+                    for (int u = 0; u < U; ++u) {
+                        // lanes past the end of the piece re-read its last item; their values are not used
+                        const uint32_t idx = from_lane(cur_idx, min(u0 + u, cnt - 1));
+                        const rsrc_t r = row_f32(grads, idx, D, col0);
 #pragma unroll
-                    for (int i = 0; i < NC; ++i) {
-                        g[u][i] = float4{0, 0, 0, 0};
-                        if (live && c.on[i]) g[u][i] = ld4(grads + (size_t)idx * D + c.col[i]);
+                        for (int i = 0; i < NC; ++i) g[u][i] = ld2(r, i);
                     }
-                }
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    if (cur + u < end) {
+                    for (int u = 0; u < U; ++u) {
+                        if (u0 + u < cnt) {
 #pragma unroll
-                        for (int i = 0; i < NC; ++i) {
-                            if (STEPS) step4(G[i], acc[i], g[u][i], lr, eps);
-                            else sumsq4(acc[i], g[u][i]);
+                            for (int i = 0; i < NC; ++i) {
+                                if (STEPS) step2(G[i], acc[i], g[u][i], lr, eps);
+                                else sumsq2(acc[i], g[u][i]);
+                            }
                         }
                     }
                 }
             }
 #pragma unroll
-            for (int i = 0; i < NC; ++i)
-                if (c.on[i]) std4(partial + (size_t)pc * D + c.col[i], acc[i]);
+            for (int i = 0; i < NC; ++i) std2(part, i, acc[i]);
         }
     }
 }
 
 // Phase 2: exclusive scan of the pieces' sums of squares, seeded with the stored accumulator;
-// long_res[slot][1] receives the accumulator after the whole run.
+// long_res[slot][1] receives the accumulator after the whole run.  One wave per long row.
 template <int NC>
 __global__ __launch_bounds__(256) void long_scan_kernel(const uint32_t *sk, const float *A, Header *hdr,
                                                         const uint32_t *long_head, const uint32_t *long_count,
@@ -206,24 +220,40 @@ __global__ __launch_bounds__(256) void long_scan_kernel(const uint32_t *sk, cons
     if (hdr->batch_bad) return;
     const uint32_t nl = min(hdr->n_long, max_slots);
     const uint32_t D = geo.D;
-    for (uint32_t slot = group_id(); slot < nl; slot += group_count()) {
-        const uint32_t x = sk[long_head[slot]];
-        const uint32_t P = long_count[slot], base = long_base[slot];
+    constexpr uint32_t U = 8;
+    for (uint32_t slot = wave_id(); slot < nl; slot += wave_count()) {
+        const uint32_t x = uniform(sk[long_head[slot]]);
+        const uint32_t P = uniform(long_count[slot]), base = uniform(long_base[slot]);
         for (uint32_t cb = 0; cb < geo.ncb; ++cb) {
-            const Cols c = lane_cols<NC>(D, cb);
+            const uint32_t col0 = cb * NC * 128u;
+            const rsrc_t arow = row_f32(A, x, D, col0);
+            D2 G[NC];
 #pragma unroll
-            for (int i = 0; i < NC; ++i) {
-                if (!c.on[i]) continue;
-                D4 G = widen4(ld4(A + (size_t)x * D + c.col[i]));
-                double *p = partial + (size_t)base * D + c.col[i];
-                for (uint32_t j = 0; j < P; ++j, p += D) {
-                    const D4 t = ldd4(p);
-                    std4(p, G);
+            for (int i = 0; i < NC; ++i) G[i] = widen2(ld2(arow, i));
+            for (uint32_t j0 = 0; j0 < P; j0 += U) {
+                D2 t[U][NC];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) G.v[q] += t.v[q];
+                for (uint32_t u = 0; u < U; ++u) {
+                    const rsrc_t r = row_f64(partial, base + min(j0 + u, P - 1), D, col0);
+#pragma unroll
+                    for (int i = 0; i < NC; ++i) t[u][i] = ldd2(r, i);
                 }
-                std4(long_res + ((size_t)slot * 2 + 1) * D + c.col[i], G);
+#pragma unroll
+                for (uint32_t u = 0; u < U; ++u) {
+                    if (j0 + u < P) {
+                        const rsrc_t r = row_f64(partial, base + j0 + u, D, col0);
+#pragma unroll
+                        for (int i = 0; i < NC; ++i) {
+                            std2(r, i, G[i]);
+                            G[i].x += t[u][i].x;
+                            G[i].y += t[u][i].y;
+                        }
+                    }
+                }
             }
+            const rsrc_t res = row_f64(long_res, (size_t)slot * 2 + 1, D, col0);
+#pragma unroll
+            for (int i = 0; i < NC; ++i) std2(res, i, G[i]);
         }
     }
 }
@@ -237,22 +267,36 @@ __global__ __launch_bounds__(256) void long_reduce_kernel(Header *hdr, const uin
     if (hdr->batch_bad) return;
     const uint32_t nl = min(hdr->n_long, max_slots);
     const uint32_t D = geo.D;
-    for (uint32_t slot = group_id(); slot < nl; slot += group_count()) {
-        const uint32_t P = long_count[slot], base = long_base[slot];
+    constexpr uint32_t U = 8;
+    for (uint32_t slot = wave_id(); slot < nl; slot += wave_count()) {
+        const uint32_t P = uniform(long_count[slot]), base = uniform(long_base[slot]);
         for (uint32_t cb = 0; cb < geo.ncb; ++cb) {
-            const Cols c = lane_cols<NC>(D, cb);
+            const uint32_t col0 = cb * NC * 128u;
+            D2 s[NC];
 #pragma unroll
-            for (int i = 0; i < NC; ++i) {
-                if (!c.on[i]) continue;
-                D4 s = D4{{0, 0, 0, 0}};
-                const double *p = partial + (size_t)base * D + c.col[i];
-                for (uint32_t j = 0; j < P; ++j, p += D) {
-                    const D4 t = ldd4(p);
+            for (int i = 0; i < NC; ++i) s[i] = D2{0, 0};
+            for (uint32_t j0 = 0; j0 < P; j0 += U) {
+                D2 t[U][NC];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) s.v[q] += t.v[q];
+                for (uint32_t u = 0; u < U; ++u) {
+                    const rsrc_t r = row_f64(partial, base + min(j0 + u, P - 1), D, col0);
+#pragma unroll
+                    for (int i = 0; i < NC; ++i) t[u][i] = ldd2(r, i);
                 }
-                std4(long_res + ((size_t)slot * 2 + 0) * D + c.col[i], s);
+#pragma unroll
+                for (uint32_t u = 0; u < U; ++u) {
+                    if (j0 + u < P) {
+#pragma unroll
+                        for (int i = 0; i < NC; ++i) {
+                            s[i].x += t[u][i].x;
+                            s[i].y += t[u][i].y;
+                        }
+                    }
+                }
             }
+            const rsrc_t res = row_f64(long_res, (size_t)slot * 2 + 0, D, col0);
+#pragma unroll
+            for (int i = 0; i < NC; ++i) std2(res, i, s[i]);
         }
     }
 }
@@ -274,118 +318,226 @@ struct ApplyArgs {
     Geometry geo;
 };
 
-// Processes the stripe whose first item sits at sorted position `pos`, for column block cb.
-// Returns the position of the first item of the next stripe.
+// General path: the stripe whose first item sits at sorted position `pos` (wave-uniform), walked
+// through memory.  Used when the stripe does not fit the wave's window: runs of more than a few
+// dozen updates, and entries whose totals come from the split-chain path.
 template <int NC>
-__device__ __forceinline__ uint32_t apply_one_stripe(const ApplyArgs &a, uint32_t pos, uint32_t cb)
+__device__ __forceinline__ void apply_stripe_general(const ApplyArgs &a, uint32_t pos, uint32_t cb)
 {
     const uint32_t D = a.geo.D, k = a.geo.k, n = a.n;
     const double lr = (double)a.geo.lr, eps = (double)a.geo.eps;
-    const Cols c = lane_cols<NC>(D, cb);
-    uint32_t key = a.sk[pos];
+    const uint32_t col0 = cb * NC * 128u;
+    uint32_t key = uniform(a.sk[pos]);
     const uint32_t g = key / k;
+    const rsrc_t perow = row_f32(a.PE, g, D, col0), parow = row_f32(a.PA, g, D, col0);
 
-    D4 pe[NC], pa[NC];
+    D2 pe[NC], pa[NC];
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
-        pe[i] = D4{{0, 0, 0, 0}};
-        pa[i] = D4{{0, 0, 0, 0}};
-        if (c.on[i]) {
-            pe[i] = widen4(ld4(a.PE + (size_t)g * D + c.col[i]));
-            pa[i] = widen4(ld4(a.PA + (size_t)g * D + c.col[i]));
-        }
+        pe[i] = widen2(ld2(perow, i));
+        pa[i] = widen2(ld2(parow, i));
     }
-
     uint32_t cur = pos;
     do {
         const uint32_t x = key;                      // a new entry of this stripe starts at cur
-        const bool is_long = (cur + kLongRun < n) && (a.sk[cur + kLongRun] == x);
-        float4 e[NC], a0[NC];
+        const bool is_long = (cur + kLongRun < n) && (uniform(a.sk[cur + kLongRun]) == x);
+        const rsrc_t erow = row_f32(a.E, x, D, col0), arow = row_f32(a.A, x, D, col0);
+        float2 e[NC], a0[NC];
 #pragma unroll
         for (int i = 0; i < NC; ++i) {
-            e[i] = float4{0, 0, 0, 0};
-            a0[i] = float4{0, 0, 0, 0};
-            if (c.on[i]) {
-                e[i] = ld4(a.E + (size_t)x * D + c.col[i]);
-                a0[i] = ld4(a.A + (size_t)x * D + c.col[i]);
-            }
+            e[i] = ld2(erow, i);
+            a0[i] = ld2(arow, i);
         }
-        D4 G[NC], acc[NC];
+        D2 G[NC], acc[NC];
         if (is_long) {
-            const uint32_t slot = a.long_slot[cur];
+            const uint32_t slot = uniform(a.long_slot[cur]);
+            const rsrc_t r0 = row_f64(a.long_res, (size_t)slot * 2 + 0, D, col0);
+            const rsrc_t r1 = row_f64(a.long_res, (size_t)slot * 2 + 1, D, col0);
 #pragma unroll
             for (int i = 0; i < NC; ++i) {
-                acc[i] = D4{{0, 0, 0, 0}};
-                G[i] = D4{{0, 0, 0, 0}};
-                if (c.on[i]) {
-                    acc[i] = ldd4(a.long_res + ((size_t)slot * 2 + 0) * D + c.col[i]);
-                    G[i] = ldd4(a.long_res + ((size_t)slot * 2 + 1) * D + c.col[i]);
-                }
+                acc[i] = ldd2(r0, i);
+                G[i] = ldd2(r1, i);
             }
-            cur += a.long_len[slot];
+            cur += uniform(a.long_len[slot]);
         } else {
 #pragma unroll
             for (int i = 0; i < NC; ++i) {
-                G[i] = widen4(a0[i]);
-                acc[i] = D4{{0, 0, 0, 0}};
+                G[i] = widen2(a0[i]);
+                acc[i] = D2{0, 0};
             }
-            float4 gr[NC];
-            {
-                const uint32_t idx = a.si[cur];
+            // the run is at most kLongRun long: walk it 64 positions at a time, U gradients in flight
+            constexpr int U = 8;
+            bool done = false;
+            while (!done) {
+                const uint32_t lane = lane_id();
+                const uint32_t wk = cur + lane < n ? a.sk[cur + lane] : kNoKey;
+                const uint32_t wi = cur + lane < n ? a.si[cur + lane] : 0u;
+                const unsigned long long other = ~__ballot(wk == x);
+                const uint32_t cnt = other ? lowest_bit(other) : (uint32_t)kWave;   // leading run of x
+                done = cnt < kWave;
+                for (uint32_t u0 = 0; u0 < cnt; u0 += U) {
+                    float2 gr[U][NC];
 #pragma unroll
-                for (int i = 0; i < NC; ++i) {
-                    gr[i] = float4{0, 0, 0, 0};
-                    if (c.on[i]) gr[i] = ld4(a.grads + (size_t)idx * D + c.col[i]);
+                    for (int u = 0; u < U; ++u) {
+                        const uint32_t idx = from_lane(wi, min(u0 + u, cnt - 1));
+                        const rsrc_t r = row_f32(a.grads, idx, D, col0);
+#pragma unroll
+                        for (int i = 0; i < NC; ++i) gr[u][i] = ld2(r, i);
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        if (u0 + u < cnt) {
+#pragma unroll
+                            for (int i = 0; i < NC; ++i) step2(G[i], acc[i], gr[u][i], lr, eps);
+                        }
                 }
-            }
-            while (true) {
-                ++cur;
-                const bool same = (cur < n) && (a.sk[cur] == x);
-                float4 nx[NC];
-#pragma unroll
-                for (int i = 0; i < NC; ++i) nx[i] = float4{0, 0, 0, 0};
-                if (same) {                           // next gradient in flight while this one is used
-                    const uint32_t idx = a.si[cur];
-#pragma unroll
-                    for (int i = 0; i < NC; ++i)
-                        if (c.on[i]) nx[i] = ld4(a.grads + (size_t)idx * D + c.col[i]);
-                }
-#pragma unroll
-                for (int i = 0; i < NC; ++i) step4(G[i], acc[i], gr[i], lr, eps);
-                if (!same) break;
-#pragma unroll
-                for (int i = 0; i < NC; ++i) gr[i] = nx[i];
+                cur += cnt;
             }
         }
-        // entry and accumulator: one rounding each; parity: add the differences
 #pragma unroll
         for (int i = 0; i < NC; ++i) {
-            if (!c.on[i]) continue;
-            const D4 e64 = widen4(e[i]), a64 = widen4(a0[i]);
-            D4 en;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                en.v[q] = e64.v[q] - acc[i].v[q];
-                pe[i].v[q] -= acc[i].v[q];
-                pa[i].v[q] += G[i].v[q] - a64.v[q];
-            }
-            st4(a.E + (size_t)x * D + c.col[i], narrow4(en));
-            st4(a.A + (size_t)x * D + c.col[i], narrow4(G[i]));
+            const D2 e64 = widen2(e[i]), a64 = widen2(a0[i]);
+            st2(erow, i, narrow2(D2{e64.x - acc[i].x, e64.y - acc[i].y}));
+            st2(arow, i, narrow2(G[i]));
+            pe[i].x -= acc[i].x;
+            pe[i].y -= acc[i].y;
+            pa[i].x += G[i].x - a64.x;
+            pa[i].y += G[i].y - a64.y;
         }
-        key = cur < n ? a.sk[cur] : kNoKey;
+        key = cur < n ? uniform(a.sk[cur]) : kNoKey;
     } while (cur < n && key / k == g);
 
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
-        if (!c.on[i]) continue;
-        st4(a.PE + (size_t)g * D + c.col[i], narrow4(pe[i]));
-        st4(a.PA + (size_t)g * D + c.col[i], narrow4(pa[i]));
+        st2(perow, i, narrow2(pe[i]));
+        st2(parow, i, narrow2(pa[i]));
     }
-    return cur;
+}
+
+// Loads of one entry's work: its row of E and A, its first gradient, and -- when it opens a
+// stripe -- the stripe's parity rows.
+template <int NC>
+struct RowLoads {
+    float2 e[NC], a[NC], g[NC], pe[NC], pa[NC];
+    uint32_t x, j;
+    bool opens;
+};
+
+template <int NC>
+__device__ __forceinline__ void issue_row(RowLoads<NC> &r, const ApplyArgs &a, uint32_t col0, uint32_t wkey,
+                                          uint32_t widx, unsigned long long stripeheads, uint32_t j)
+{
+    const uint32_t D = a.geo.D;
+    r.j = j;
+    r.x = from_lane(wkey, j);
+    r.opens = (stripeheads >> j) & 1ull;
+    const uint32_t idx = from_lane(widx, j);
+    const rsrc_t arow = row_f32(a.A, r.x, D, col0), grow = row_f32(a.grads, idx, D, col0),
+                 erow = row_f32(a.E, r.x, D, col0);
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        r.a[i] = ld2(arow, i);
+        r.g[i] = ld2(grow, i);
+        r.e[i] = ld2(erow, i);
+        r.pe[i] = r.pa[i] = float2{0, 0};
+    }
+    if (r.opens) {
+        const uint32_t g = r.x / a.geo.k;
+        const rsrc_t perow = row_f32(a.PE, g, D, col0), parow = row_f32(a.PA, g, D, col0);
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+            r.pe[i] = ld2(perow, i);
+            r.pa[i] = ld2(parow, i);
+        }
+    }
+}
+
+// Window path: every stripe that opens in the first kChunk lanes of the wave's 64-position window
+// and ends inside the window.  Entries are taken one after the other; the loads of the next entry
+// are issued before the current one is computed, so two entries' rows are in flight per wave.
+template <int NC>
+__device__ __forceinline__ void apply_window(const ApplyArgs &a, uint32_t wkey, uint32_t widx,
+                                             unsigned long long rowheads, unsigned long long stripeheads,
+                                             uint32_t first, uint32_t end, uint32_t cb)
+{
+    const uint32_t D = a.geo.D, k = a.geo.k;
+    const double lr = (double)a.geo.lr, eps = (double)a.geo.eps;
+    const uint32_t col0 = cb * NC * 128u;
+    unsigned long long todo = rowheads & bits_below(end) & ~bits_below(first);
+    if (!todo) return;
+    RowLoads<NC> nxt;
+    issue_row<NC>(nxt, a, col0, wkey, widx, stripeheads, lowest_bit(todo));
+    todo &= todo - 1ull;
+    D2 pe[NC], pa[NC];
+#pragma unroll
+    for (int i = 0; i < NC; ++i) pe[i] = pa[i] = D2{0, 0};
+    while (true) {
+        const RowLoads<NC> cur = nxt;
+        const bool has_next = todo != 0ull;
+        uint32_t rend = end;
+        if (has_next) {
+            rend = lowest_bit(todo);
+            todo &= todo - 1ull;
+            issue_row<NC>(nxt, a, col0, wkey, widx, stripeheads, rend);
+        }
+        D2 G[NC], acc[NC];
+        float2 gr[NC];
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+            G[i] = widen2(cur.a[i]);
+            acc[i] = D2{0, 0};
+            gr[i] = cur.g[i];
+        }
+        for (uint32_t t = cur.j;;) {                  // the entry's updates, in arrival order
+            const bool more = t + 1 < rend;
+            float2 nx[NC];
+#pragma unroll
+            for (int i = 0; i < NC; ++i) nx[i] = float2{0, 0};
+            if (more) {
+                const rsrc_t r = row_f32(a.grads, from_lane(widx, t + 1), D, col0);
+#pragma unroll
+                for (int i = 0; i < NC; ++i) nx[i] = ld2(r, i);
+            }
+#pragma unroll
+            for (int i = 0; i < NC; ++i) step2(G[i], acc[i], gr[i], lr, eps);
+            if (!more) break;
+#pragma unroll
+            for (int i = 0; i < NC; ++i) gr[i] = nx[i];
+            ++t;
+        }
+        if (cur.opens) {
+#pragma unroll
+            for (int i = 0; i < NC; ++i) {
+                pe[i] = widen2(cur.pe[i]);
+                pa[i] = widen2(cur.pa[i]);
+            }
+        }
+        const rsrc_t erow = row_f32(a.E, cur.x, D, col0), arow = row_f32(a.A, cur.x, D, col0);
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+            const D2 e64 = widen2(cur.e[i]), a64 = widen2(cur.a[i]);
+            st2(erow, i, narrow2(D2{e64.x - acc[i].x, e64.y - acc[i].y}));
+            st2(arow, i, narrow2(G[i]));
+            pe[i].x -= acc[i].x;
+            pe[i].y -= acc[i].y;
+            pa[i].x += G[i].x - a64.x;
+            pa[i].y += G[i].y - a64.y;
+        }
+        if (!has_next || nxt.opens) {                 // last entry of its stripe: the parity rows are complete
+            const uint32_t g = cur.x / k;
+            const rsrc_t perow = row_f32(a.PE, g, D, col0), parow = row_f32(a.PA, g, D, col0);
+#pragma unroll
+            for (int i = 0; i < NC; ++i) {
+                st2(perow, i, narrow2(pe[i]));
+                st2(parow, i, narrow2(pa[i]));
+            }
+        }
+        if (!has_next) break;
+    }
 }
 
 template <int NC>
-__global__ __launch_bounds__(256) void apply_stripes_kernel(ApplyArgs a)
+__device__ __forceinline__ void apply_stripes_body(const ApplyArgs &a)
 {
     if (a.hdr->batch_bad) return;
     // the batch is valid: publish its per-server counts
@@ -396,27 +548,58 @@ __global__ __launch_bounds__(256) void apply_stripes_kernel(ApplyArgs a)
             a.load_parity[i] += a.cnt[S + i];
         }
     }
-    const uint32_t n = a.n, k = a.geo.k;
+    const uint32_t n = a.n, k = a.geo.k, lane = lane_id();
     const uint32_t nchunks = (n + kChunk - 1) / kChunk;
-    for (uint32_t ch = group_id(); ch < nchunks; ch += group_count()) {
-        uint32_t pos = ch * kChunk;
-        const uint32_t own_end = min(pos + kChunk, n);
-        if (pos > 0) {
-            // items at the front that belong to a stripe that started in an earlier chunk
-            const uint32_t gprev = a.sk[pos - 1] / k;
-            while (pos < own_end && a.sk[pos] / k == gprev) ++pos;
-        }
-        while (pos < own_end) {
-            uint32_t next = pos;
-            for (uint32_t cb = 0; cb < a.geo.ncb; ++cb) next = apply_one_stripe<NC>(a, pos, cb);
-            pos = next;
+    for (uint32_t ch = wave_id(); ch < nchunks; ch += wave_count()) {
+        const uint32_t p0 = ch * kChunk;
+        const uint32_t wkey = p0 + lane < n ? a.sk[p0 + lane] : kNoKey;
+        const uint32_t widx = p0 + lane < n ? a.si[p0 + lane] : 0u;
+        const uint32_t prevk = p0 ? uniform(a.sk[p0 - 1]) : kNoKey;
+        uint32_t left = __shfl_up(wkey, 1, kWave);
+        if (lane == 0) left = prevk;
+        const bool valid = wkey != kNoKey;
+        const bool rh = !valid || left == kNoKey || left != wkey;      // lanes past n end the last run
+        const bool sh = valid && (left == kNoKey || left / k != wkey / k);
+        const unsigned long long rowheads = __ballot(rh);
+        const unsigned long long stripeheads = __ballot(sh);
+        const uint32_t vend = min((uint32_t)kWave, n - p0);
+        const unsigned long long owned = stripeheads & bits_below(kChunk);
+        if (!owned) continue;
+        const uint32_t first = lowest_bit(owned);
+        const uint32_t last = 63u - (uint32_t)__builtin_clzll(owned);
+        const unsigned long long after = stripeheads & ~bits_below(last + 1);
+        const bool last_inside = after != 0ull || p0 + kWave >= n;
+        const uint32_t end = last_inside ? (after ? lowest_bit(after) : vend) : last;
+        for (uint32_t cb = 0; cb < a.geo.ncb; ++cb) {
+            apply_window<NC>(a, wkey, widx, rowheads, stripeheads, first, end, cb);
+            if (!last_inside) apply_stripe_general<NC>(a, p0 + last, cb);
         }
     }
+}
+
+// D <= 128
+__global__ __launch_bounds__(256) void apply_stripes_kernel_d128(ApplyArgs a)
+{
+    apply_stripes_body<1>(a);
+}
+// D > 128: two 128-float slices per lane.
+__global__ __launch_bounds__(256) void apply_stripes_kernel_d256(ApplyArgs a)
+{
+    apply_stripes_body<2>(a);
 }
 
 // ================================================================================================
 // encode and route
 // ================================================================================================
+
+struct D4 { double v[4]; };
+__device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ __forceinline__ void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+__device__ __forceinline__ D4 widen4(float4 f) { return D4{{(double)f.x, (double)f.y, (double)f.z, (double)f.w}}; }
+__device__ __forceinline__ float4 narrow4(const D4 &d)
+{
+    return float4{(float)d.v[0], (float)d.v[1], (float)d.v[2], (float)d.v[3]};
+}
 
 __global__ __launch_bounds__(256) void encode_kernel(const float *E, const float *A, float *PE, float *PA,
                                                      uint32_t stripes, uint32_t D, uint32_t k)
@@ -466,21 +649,36 @@ __global__ __launch_bounds__(256) void route_kernel(const uint64_t *keys, uint64
 // host side
 // ================================================================================================
 
+// Blocks of 256 threads of `kernel` that are resident on the whole device at once: the grid-stride
+// kernels are launched with exactly that many, so that every block starts at time zero.
+template <typename K>
+static int resident_grid(K kernel, int cus)
+{
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess || per_cu < 1) per_cu = 4;
+    return cus * per_cu;
+}
+
 void launch_chains(const Scratch &s, const Geometry &g, const float *A, const float *grads,
                    const uint32_t *sk, const uint32_t *si, uint32_t n, uint32_t max_slots,
-                   uint32_t max_pieces, int grid_blocks, hipStream_t st)
+                   uint32_t max_pieces, int cus, hipStream_t st)
 {
     if (n <= kLongRun) return;    // no row can have more than kLongRun updates
-    const dim3 grid(grid_blocks), block(256);
+    static int grid_p1[3] = {0, 0, 0}, grid_p3[3] = {0, 0, 0};
+    if (!grid_p1[g.nc]) {
+        grid_p1[g.nc] = g.nc == 1 ? resident_grid(long_piece_kernel<1, false>, cus) : resident_grid(long_piece_kernel<2, false>, cus);
+        grid_p3[g.nc] = g.nc == 1 ? resident_grid(long_piece_kernel<1, true>, cus) : resident_grid(long_piece_kernel<2, true>, cus);
+    }
+    const dim3 grid(cus * 8), block(256), gridp1(grid_p1[g.nc]), gridp3(grid_p3[g.nc]);
     hipLaunchKernelGGL(long_find_kernel, grid, block, 0, st, sk, n, s.hdr, s.long_slot, s.long_head, max_slots);
     hipLaunchKernelGGL(long_plan_kernel, grid, block, 0, st, sk, n, s.hdr, s.long_head, s.long_len, s.long_piece,
                        s.long_count, s.long_base, s.piece_slot, max_slots, max_pieces);
 #define ECRM_CHAIN_LAUNCH(NC)                                                                               \
-    hipLaunchKernelGGL((long_piece_kernel<NC, false>), grid, block, 0, st, si, grads, s.hdr, s.long_head,   \
+    hipLaunchKernelGGL((long_piece_kernel<NC, false>), gridp1, block, 0, st, si, grads, s.hdr, s.long_head, \
                        s.long_len, s.long_piece, s.long_base, s.piece_slot, s.partial, max_pieces, g);      \
     hipLaunchKernelGGL((long_scan_kernel<NC>), grid, block, 0, st, sk, A, s.hdr, s.long_head, s.long_count, \
                        s.long_base, s.partial, s.long_res, max_slots, g);                                   \
-    hipLaunchKernelGGL((long_piece_kernel<NC, true>), grid, block, 0, st, si, grads, s.hdr, s.long_head,    \
+    hipLaunchKernelGGL((long_piece_kernel<NC, true>), gridp3, block, 0, st, si, grads, s.hdr, s.long_head,  \
                        s.long_len, s.long_piece, s.long_base, s.piece_slot, s.partial, max_pieces, g);      \
     hipLaunchKernelGGL((long_reduce_kernel<NC>), grid, block, 0, st, s.hdr, s.long_count, s.long_base,      \
                        s.partial, s.long_res, max_slots, g);
@@ -490,8 +688,11 @@ void launch_chains(const Scratch &s, const Geometry &g, const float *A, const fl
 
 void launch_apply(const Scratch &s, const Geometry &g, float *E, float *A, float *PE, float *PA,
                   unsigned long long *load_data, unsigned long long *load_parity, const float *grads,
-                  const uint32_t *sk, const uint32_t *si, uint32_t n, int grid_blocks, hipStream_t st)
+                  const uint32_t *sk, const uint32_t *si, uint32_t n, int cus, hipStream_t st)
 {
+    static int grid_apply[3] = {0, 0, 0};
+    if (!grid_apply[g.nc])
+        grid_apply[g.nc] = g.nc == 1 ? resident_grid(apply_stripes_kernel_d128, cus) : resident_grid(apply_stripes_kernel_d256, cus);
     ApplyArgs a;
     a.E = E; a.A = A; a.PE = PE; a.PA = PA;
     a.grads = grads; a.sk = sk; a.si = si;
@@ -499,9 +700,9 @@ void launch_apply(const Scratch &s, const Geometry &g, float *E, float *A, float
     a.hdr = s.hdr; a.cnt = s.cnt;
     a.load_data = load_data; a.load_parity = load_parity;
     a.n = n; a.geo = g;
-    const dim3 grid(grid_blocks), block(256);
-    if (g.nc == 1) hipLaunchKernelGGL(apply_stripes_kernel<1>, grid, block, 0, st, a);
-    else hipLaunchKernelGGL(apply_stripes_kernel<2>, grid, block, 0, st, a);
+    const dim3 grid(grid_apply[g.nc]), block(256);
+    if (g.nc == 1) hipLaunchKernelGGL(apply_stripes_kernel_d128, grid, block, 0, st, a);
+    else hipLaunchKernelGGL(apply_stripes_kernel_d256, grid, block, 0, st, a);
 }
 
 void launch_encode(const Geometry &g, const float *E, const float *A, float *PE, float *PA,
