@@ -37,6 +37,14 @@ def main():
     ap.add_argument("--workload", default="hbm_scale")
     ap.add_argument("--scale-shift", type=int, default=0, help="halve n and R this many times (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layout", default="arena", choices=["arena", "arena-rev", "arena-spread", "separate"])
+    ap.add_argument("--pads", default="", help="arena only: GiB of padding after E, A, PE (comma separated)")
+    ap.add_argument("--order", default="E,g0,g1,A,g2,g3,PE,PA,scratch,keys,g*",
+                    help="arena only: order of the resident arrays (gN = batch N, padN = N GiB of padding)")
+    ap.add_argument("--skew", type=int, default=0,
+                    help="extra bytes (multiple of 256) by which each successive resident array is shifted")
+    ap.add_argument("--per-step", action="store_true",
+                    help="diagnostic: after the timed region, run the steps again one by one and log each one's phases")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (all servers' shards in one HBM); "
@@ -64,22 +72,86 @@ def main():
     seed = w["seed"]
 
     t_setup = time.perf_counter()
-    E = si.table(seed, si.TAG_E0, R, D, dev)
-    A = si.table(seed, si.TAG_A0, R, D, dev)
-    PE = torch.empty(R // k, D, device=dev)
-    PA = torch.empty(R // k, D, device=dev)
-    ld = torch.zeros(S, dtype=torch.int64, device=dev)
-    lp = torch.zeros(S, dtype=torch.int64, device=dev)
     ctx = Ecrm(R, D, k, S, si.DEFAULT_LR, si.DEFAULT_EPS, per)
-    scratch = torch.empty(ctx.scratch_bytes(), dtype=torch.uint8, device=dev)
+    # one arena for everything that stays resident (tables, scratch, all batches), carved at 2 MiB
+    ALIGN = 2 << 20
+    sizes = {"E": R * D * 4, "A": R * D * 4, "PE": R // k * D * 4, "PA": R // k * D * 4, "ld": S * 8, "lp": S * 8,
+             "scratch": ctx.scratch_bytes()}
+    for b in range(nb):
+        sizes[f"keys{b}"] = per * 8
+        sizes[f"grads{b}"] = per * D * 4
+    if args.layout == "arena-rev":
+        sizes = dict(reversed(list(sizes.items())))
+    if args.layout == "arena-spread":          # the four tables far apart, batches in between
+        order, gi = [], 0
+        per_gap = max(1, nb // 4)
+        for t in ("E", "A", "PE", "PA"):
+            order.append(t)
+            for _ in range(per_gap):
+                if gi < nb:
+                    order.append(f"grads{gi}")
+                    gi += 1
+        order += [f"grads{b}" for b in range(gi, nb)] + [f"keys{b}" for b in range(nb)] + ["scratch", "ld", "lp"]
+        sizes = {name: sizes[name] for name in order}
+    if args.order:
+        order, npad = [], 0
+        for tok in args.order.split(","):
+            if tok == "g*":
+                order += [f"grads{b}" for b in range(nb) if f"grads{b}" not in order]
+            elif tok == "keys":
+                order += [f"keys{b}" for b in range(nb)]
+            elif tok.startswith("pad"):
+                sizes[f"_pad{npad}"] = int(float(tok[3:]) * (1 << 30))
+                order.append(f"_pad{npad}")
+                npad += 1
+            elif tok.startswith("g"):
+                if int(tok[1:]) < nb:
+                    order.append(f"grads{int(tok[1:])}")
+            else:
+                order.append(tok)
+        order += [n_ for n_ in sizes if n_ not in order]
+        sizes = {name: sizes[name] for name in order}
+    pads = dict(zip(("E", "A", "PE"), [int(float(x) * (1 << 30)) for x in args.pads.split(",")])) if args.pads else {}
+    offs, total = {}, 0
+    for i, (name, sz) in enumerate(sizes.items()):
+        offs[name] = total + i * args.skew
+        total += (sz + ALIGN - 1) // ALIGN * ALIGN + pads.get(name, 0)
+    total += len(sizes) * args.skew
+    if args.layout == "separate":
+        pieces = {name: torch.empty(sz, dtype=torch.uint8, device=dev) for name, sz in sizes.items()}
+
+        def carve(name, dtype, shape):
+            return pieces[name].view(dtype).view(shape)
+    else:
+        arena = torch.empty(total, dtype=torch.uint8, device=dev)
+
+        def carve(name, dtype, shape):
+            return arena[offs[name]:offs[name] + sizes[name]].view(dtype).view(shape)
+
+    E, A = carve("E", torch.float32, (R, D)), carve("A", torch.float32, (R, D))
+    PE, PA = carve("PE", torch.float32, (R // k, D)), carve("PA", torch.float32, (R // k, D))
+    ld, lp = carve("ld", torch.int64, (S,)), carve("lp", torch.int64, (S,))
+    scratch = carve("scratch", torch.uint8, (sizes["scratch"],))
+    CH = 1 << 22                                  # rows generated per slice (2 GiB of fp32 at D = 128)
+    for r0 in range(0, R, CH):
+        r1 = min(R, r0 + CH)
+        E[r0:r1] = si.values(seed, si.TAG_E0, r0 * D, (r1 - r0) * D, dev).view(r1 - r0, D)
+        A[r0:r1] = si.values(seed, si.TAG_A0, r0 * D, (r1 - r0) * D, dev).view(r1 - r0, D)
+    ld.zero_()
+    lp.zero_()
     ctx.bind(E, A, PE, PA, ld, lp, scratch)
     ctx.encode()
 
     keys, grads, alg_path, alg_apply = [], [], [], []
     for b in range(nb):
-        kt = si.workload_keys_t(args.workload, b, sh, dev)
+        kt = carve(f"keys{b}", torch.int64, (per,))
+        kt.copy_(si.workload_keys_t(args.workload, b, sh, dev))
         keys.append(kt)
-        grads.append(si.grads(seed, b * per, per, D, dev))
+        gt = carve(f"grads{b}", torch.float32, (per, D))
+        for i0 in range(0, per, CH):
+            i1 = min(per, i0 + CH)
+            gt[i0:i1] = si.grads(seed, b * per + i0, i1 - i0, D, dev)
+        grads.append(gt)
         # measurement only: rows / stripes this batch touches, items on rows with long runs
         uk, cnt = torch.unique(kt, return_counts=True)
         U = int(uk.numel())
@@ -113,6 +185,14 @@ def main():
     ms, calls = ctx.profile_read()
     ctx.profile(False)
     assert ctx.status() == 0 and calls == min(args.steps, 256)
+
+    if args.per_step:
+        ctx.profile(True)
+        for i in range(args.steps):
+            ctx.update(keys[i % nb], grads[i % nb])
+            pms, _ = ctx.profile_read()
+            log(f"step {i:3d} batch {i % nb:2d}: group {pms[0]:.3f} chains {pms[1]:.3f} apply {pms[2]:.3f} ms")
+        ctx.profile(False)
 
     elapsed = t1 - t0
     items = per * args.steps

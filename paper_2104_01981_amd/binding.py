@@ -13,7 +13,7 @@ ECRM_OK, ECRM_EINVAL, ECRM_ENOTBOUND, ECRM_ESCRATCH, ECRM_EBATCH, ECRM_EKEYRANGE
 ECRM_PHASES = 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libecrm.so")
+_LIB_PATH = os.environ.get("ECRM_LIBRARY") or os.path.join(_HERE, "libecrm.so")
 _lib = None
 
 SYMBOLS = ["ecrm_create", "ecrm_destroy", "ecrm_data_bytes", "ecrm_parity_bytes", "ecrm_scratch_bytes",

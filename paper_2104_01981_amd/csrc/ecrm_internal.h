@@ -20,7 +20,10 @@ constexpr int kMaxBins = 1 << kMaxRadixBits;
 constexpr uint32_t kLongRun = ECRM_LONG_RUN;  // rows with more updates than this use the split-chain path
 constexpr uint32_t kPieceMin = 128;  // smallest chain piece
 constexpr uint32_t kPieceMaxCount = 1024;     // a chain is cut into at most this many pieces
-constexpr uint32_t kChunk = 32;      // sorted positions whose stripes one wave owns per grid-stride step
+#ifndef ECRM_CHUNK
+#define ECRM_CHUNK 16
+#endif
+constexpr uint32_t kChunk = ECRM_CHUNK;   // sorted positions whose stripes one wave owns per grid-stride step (<= 63)
 constexpr uint32_t kNoKey = 0xFFFFFFFFu;
 
 // ---- device-side header at the start of the scratch buffer --------------------------------------

@@ -40,14 +40,28 @@ __device__ __forceinline__ rsrc_t row_f64(const double *table, size_t row, uint3
 }
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+// Cache policy of the row accesses (buffer instruction aux bits; 2 = non-temporal).  Every row is
+// read once and written at most once per call, so nothing is worth keeping in L2 or the MALL;
+// streaming hints measured 4 % faster on the apply kernel and 10 % on the chain kernels.
+#ifndef ECRM_AUX_GRAD
+#define ECRM_AUX_GRAD 2
+#endif
+#ifndef ECRM_AUX_LOAD
+#define ECRM_AUX_LOAD 2
+#endif
+#ifndef ECRM_AUX_STORE
+#define ECRM_AUX_STORE 2
+#endif
 // lane's float2 of 128-float slice i of the row
+template <int AUX = ECRM_AUX_LOAD>
 __device__ __forceinline__ float2 ld2(rsrc_t r, int i)
 {
-    return __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(r, (int)(lane_id() * 8u + i * 512u), 0, 0));
+    return __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(r, (int)(lane_id() * 8u + i * 512u), 0, AUX));
 }
+__device__ __forceinline__ float2 ldg2(rsrc_t r, int i) { return ld2<ECRM_AUX_GRAD>(r, i); }   // gradients: read once
 __device__ __forceinline__ void st2(rsrc_t r, int i, float2 v)
 {
-    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, v), r, (int)(lane_id() * 8u + i * 512u), 0, 0);
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, v), r, (int)(lane_id() * 8u + i * 512u), 0, ECRM_AUX_STORE);
 }
 
 struct D2 { double x, y; };
@@ -189,7 +203,7 @@ __global__ __launch_bounds__(256) void long_piece_kernel(const uint32_t *si, con
                         const uint32_t idx = from_lane(cur_idx, min(u0 + u, cnt - 1));
                         const rsrc_t r = row_f32(grads, idx, D, col0);
 #pragma unroll
-                        for (int i = 0; i < NC; ++i) g[u][i] = ld2(r, i);
+                        for (int i = 0; i < NC; ++i) g[u][i] = ldg2(r, i);
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
@@ -382,7 +396,7 @@ __device__ __forceinline__ void apply_stripe_general(const ApplyArgs &a, uint32_
                         const uint32_t idx = from_lane(wi, min(u0 + u, cnt - 1));
                         const rsrc_t r = row_f32(a.grads, idx, D, col0);
 #pragma unroll
-                        for (int i = 0; i < NC; ++i) gr[u][i] = ld2(r, i);
+                        for (int i = 0; i < NC; ++i) gr[u][i] = ldg2(r, i);
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u)
@@ -437,7 +451,7 @@ __device__ __forceinline__ void issue_row(RowLoads<NC> &r, const ApplyArgs &a, u
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
         r.a[i] = ld2(arow, i);
-        r.g[i] = ld2(grow, i);
+        r.g[i] = ldg2(grow, i);
         r.e[i] = ld2(erow, i);
         r.pe[i] = r.pa[i] = float2{0, 0};
     }
@@ -496,7 +510,7 @@ __device__ __forceinline__ void apply_window(const ApplyArgs &a, uint32_t wkey, 
             if (more) {
                 const rsrc_t r = row_f32(a.grads, from_lane(widx, t + 1), D, col0);
 #pragma unroll
-                for (int i = 0; i < NC; ++i) nx[i] = ld2(r, i);
+                for (int i = 0; i < NC; ++i) nx[i] = ldg2(r, i);
             }
 #pragma unroll
             for (int i = 0; i < NC; ++i) step2(G[i], acc[i], gr[i], lr, eps);
@@ -577,8 +591,11 @@ __device__ __forceinline__ void apply_stripes_body(const ApplyArgs &a)
     }
 }
 
+#ifndef ECRM_APPLY_WAVES
+#define ECRM_APPLY_WAVES 1
+#endif
 // D <= 128
-__global__ __launch_bounds__(256) void apply_stripes_kernel_d128(ApplyArgs a)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ECRM_APPLY_WAVES, 8))) void apply_stripes_kernel_d128(ApplyArgs a)
 {
     apply_stripes_body<1>(a);
 }
@@ -656,6 +673,9 @@ static int resident_grid(K kernel, int cus)
 {
     int per_cu = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess || per_cu < 1) per_cu = 4;
+#ifdef ECRM_BLOCKS_PER_CU
+    if (per_cu > ECRM_BLOCKS_PER_CU) per_cu = ECRM_BLOCKS_PER_CU;
+#endif
     return cus * per_cu;
 }
 
