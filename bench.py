@@ -23,6 +23,25 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the apply kernel on the default workload, from rocprofv3 FETCH_SIZE and
+# WRITE_SIZE scaled by a plain copy of known size (profiles/update_path_hbm_scale_hbm_traffic.txt).
+# Reported only while the kernel's sources are the ones the counters were taken on.
+TRAFFIC_BYTES_PER_LAUNCH = 37780986941
+TRAFFIC_SOURCES = ["paper_2104_01981_amd/csrc/update.hip", "paper_2104_01981_amd/csrc/ecrm_internal.h"]
+TRAFFIC_SOURCES_SHA256 = "7e090d60a1a77ae5048b7ca60372aaef0ee74d4d59cd040e35be52afee369f61"
+
+
+def measured_traffic(workload, scale_shift):
+    import hashlib
+    h = hashlib.sha256()
+    try:
+        for rel in TRAFFIC_SOURCES:
+            h.update(open(os.path.join(ROOT, rel), "rb").read())
+    except OSError:
+        return None
+    if workload != "hbm_scale" or scale_shift or h.hexdigest() != TRAFFIC_SOURCES_SHA256:
+        return None
+    return TRAFFIC_BYTES_PER_LAUNCH
 
 
 def log(*a):
@@ -43,6 +62,8 @@ def main():
                     help="arena only: order of the resident arrays (gN = batch N, padN = N GiB of padding)")
     ap.add_argument("--skew", type=int, default=0,
                     help="extra bytes (multiple of 256) by which each successive resident array is shifted")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run plain device-to-device copies of 8 GiB (to scale rocprof's HBM byte counters)")
     ap.add_argument("--per-step", action="store_true",
                     help="diagnostic: after the timed region, run the steps again one by one and log each one's phases")
     args = ap.parse_args()
@@ -64,6 +85,15 @@ def main():
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 31, dtype=torch.float32, device=dev)      # 8 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4,
+                                             "copies": 5}}))
+        return
     w = si.WORKLOADS[args.workload]
     sh = args.scale_shift
     R, D, k, S = w["R"] >> sh, si.DEFAULT_D, si.DEFAULT_K, si.DEFAULT_S
@@ -213,7 +243,8 @@ def main():
                    "rows": R, "dim": D, "k": k, "servers": S, "storage": "f32", "optimizer": "adagrad",
                    "keys": w["kind"], "batches_resident": nb},
         "roofline": {"bound": "hbm", "kernel": "apply_stripes_kernel_d128", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic(args.workload, sh),
                      "algorithmic_bytes_per_launch": apply_bytes, "avg_launch_ms": apply_ms},
         "phases_ms_per_step": {"group": ms[0] / calls, "chains": ms[1] / calls, "apply": apply_ms},
         "path": {"algorithmic_bytes_per_step": path_bytes, "achieved_GBps": path_gbs,

@@ -65,7 +65,7 @@ int ecrm_oracle_route(const uint64_t *keys, uint64_t n, uint64_t R, uint32_t k, 
     return 0;
 }
 
-/* ---- load accounting (Sec. 3.6: every entry update is also applied to one parity; Sec. 4.2
+/* ---- load accounting (Sec. 3.6: every entry update is also applied to one parity; Sec. 4.3
  *      "Effect on load imbalance": count the updates that occur on each server) -------------- */
 
 int ecrm_oracle_load(const uint64_t *keys, uint64_t n, uint64_t R, uint32_t k, uint32_t S,
