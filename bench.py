@@ -56,6 +56,7 @@ def main():
     ap.add_argument("--workload", default="hbm_scale")
     ap.add_argument("--scale-shift", type=int, default=0, help="halve n and R this many times (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-recovery", action="store_true", help="skip the recovery-decode measurement")
     ap.add_argument("--layout", default="arena", choices=["arena", "arena-rev", "arena-spread", "separate"])
     ap.add_argument("--pads", default="", help="arena only: GiB of padding after E, A, PE (comma separated)")
     ap.add_argument("--order", default="E,g0,g1,A,g2,g3,PE,PA,scratch,keys,g*",
@@ -250,6 +251,42 @@ def main():
         "path": {"algorithmic_bytes_per_step": path_bytes, "achieved_GBps": path_gbs,
                  "frac_of_hbm_peak": path_gbs / HBM_PEAK_GBS},
     }
+
+    if not args.no_recovery:
+        # next row of the scope table: full recovery of one server and degraded reads (Sec. 3.4)
+        def timed(fn, reps=3):
+            fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+        G = R // k
+        held = sum(1 for g in range(S) for u in range(k + 1)
+                   if (g % S == 0 if u == k else (g + 1 + u) % S == 0)) / S      # units of server 0 per stripe
+        rec_ms = timed(lambda: ctx.recover_server(0))
+        rec_bytes = G * held * (k + 1) * 2 * D * 4
+        nread = min(per, 1 << 22)
+        oe = torch.empty(nread, D, device=dev)
+        oa = torch.empty(nread, D, device=dev)
+        kread = keys[0][:nread]
+        plain_ms = timed(lambda: ctx.degraded_read(kread, None, oe, oa))
+        degr_ms = timed(lambda: ctx.degraded_read(kread, 1, oe, oa))
+        lostfrac = float(((kread // k + 1 + kread % k) % S == 1).float().mean())
+        plain_bytes = nread * 4 * D * 4
+        degr_bytes = nread * (1 - lostfrac) * 4 * D * 4 + nread * lostfrac * (k + 1) * 2 * D * 4
+        assert ctx.status() == 0
+        out["recovery"] = {
+            "recover_server": {"ms": rec_ms, "algorithmic_bytes": rec_bytes, "GBps": rec_bytes / rec_ms / 1e6,
+                               "frac_of_hbm_peak": rec_bytes / rec_ms / 1e6 / HBM_PEAK_GBS,
+                               "what": "rebuild every unit server 0 holds (k reads + 1 write per stripe, E and A)"},
+            "degraded_read": {"keys": nread, "plain_ms": plain_ms, "plain_GBps": plain_bytes / plain_ms / 1e6,
+                              "lost_server_ms": degr_ms, "lost_server_GBps": degr_bytes / degr_ms / 1e6,
+                              "decoded_fraction": lostfrac},
+        }
+        del oe, oa
 
     if not args.no_cpu_baseline:
         import oracle

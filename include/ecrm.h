@@ -97,6 +97,29 @@ int ecrm_route(ecrm_ctx *ctx, const uint64_t *keys, uint64_t n, uint64_t *stripe
  * keys/grads may be reused once the stream has passed the call. */
 int ecrm_update(ecrm_ctx *ctx, const uint64_t *keys, const float *grads, uint64_t n, void *hip_stream);
 
+/* Recovery from the loss of one server (Sec. 3.4), with the subtraction decoder of Sec. 3.2:
+ * a lost entry is e_j = p - sum_{i != j} e_i (same for its accumulator), a lost parity is re-encoded.
+ * Server s holds member j of stripe g when (g+1+j) mod S == s and the parity of g when g mod S == s;
+ * the k+1 units of a stripe are on k+1 different servers, so at most one unit per stripe is lost.
+ * Sums are carried in fp64 in the order p, then minus the members by increasing j, and rounded once.
+ *
+ * ecrm_fail_server    test aid: overwrites every unit (rows of E and A, or of PE and PA) held by
+ *                     `server` with NaN, as if its memory were gone.
+ * ecrm_recover_server rebuilds every unit held by `server` from the k surviving units of its stripe
+ *                     ("full recovery").  Work enqueued earlier on the stream -- every difference of
+ *                     every earlier update -- is complete before it reads anything (Sec. 3.5).
+ * ecrm_degraded_read  reads the entries of n keys into out_E[n][D] (and their accumulators into
+ *                     out_A[n][D] if not NULL) while `lost_server` is down: rows it held are decoded on
+ *                     the fly from the parity and the other members, all others are copied.  Pass
+ *                     ECRM_NO_SERVER for a plain gather.  Keys >= rows raise the sticky EKEYRANGE
+ *                     status and leave their output rows unwritten.
+ * server >= S (other than ECRM_NO_SERVER for the read) is EINVAL. */
+#define ECRM_NO_SERVER 0xFFFFFFFFu
+int ecrm_fail_server(ecrm_ctx *ctx, uint32_t server, void *hip_stream);
+int ecrm_recover_server(ecrm_ctx *ctx, uint32_t server, void *hip_stream);
+int ecrm_degraded_read(ecrm_ctx *ctx, const uint64_t *keys, uint64_t n, uint32_t lost_server,
+                       float *out_E, float *out_A, void *hip_stream);
+
 /* Waits for the stream, then returns ECRM_OK, or EKEYRANGE if any batch since the last
  * ecrm_clear_status (or bind) carried a bad key, or EHIP if the runtime reports an error. */
 int ecrm_status(ecrm_ctx *ctx, void *hip_stream);

@@ -34,6 +34,9 @@ def lib():
         _lib.ecrm_oracle_route.restype = C.c_int
         _lib.ecrm_oracle_load.restype = C.c_int
         _lib.ecrm_oracle_max_threads.restype = C.c_int
+        _lib.ecrm_oracle_recover_server.restype = C.c_int
+        _lib.ecrm_oracle_fail_server.restype = C.c_int
+        _lib.ecrm_oracle_degraded_read.restype = C.c_int
     return _lib
 
 
@@ -91,6 +94,34 @@ def decode_member(T: np.ndarray, P: np.ndarray, k: int, lost: int) -> np.ndarray
     lib().ecrm_oracle_decode_member(_f32(T), _f32(P), C.c_uint64(R), C.c_uint32(D), C.c_uint32(k),
                                     C.c_uint32(lost), _f32(out))
     return out
+
+
+def recover_server(E, A, PE, PA, k: int, S: int, server: int) -> None:
+    R, D = E.shape
+    rc = lib().ecrm_oracle_recover_server(_f32(E), _f32(A), _f32(PE), _f32(PA), C.c_uint64(R), C.c_uint32(D),
+                                          C.c_uint32(k), C.c_uint32(S), C.c_uint32(server))
+    if rc != 0:
+        raise ValueError("bad server")
+
+
+def fail_server(E, A, PE, PA, k: int, S: int, server: int) -> None:
+    R, D = E.shape
+    rc = lib().ecrm_oracle_fail_server(_f32(E), _f32(A), _f32(PE), _f32(PA), C.c_uint64(R), C.c_uint32(D),
+                                       C.c_uint32(k), C.c_uint32(S), C.c_uint32(server))
+    if rc != 0:
+        raise ValueError("bad server")
+
+
+def degraded_read(E, A, PE, PA, k: int, S: int, keys, lost: int):
+    R, D = E.shape
+    n = len(keys)
+    oe, oa = np.empty((n, D), np.float32), np.empty((n, D), np.float32)
+    rc = lib().ecrm_oracle_degraded_read(_f32(E), _f32(A), _f32(PE), _f32(PA), C.c_uint64(R), C.c_uint32(D),
+                                         C.c_uint32(k), C.c_uint32(S), _u64(keys), C.c_uint64(n),
+                                         C.c_uint32(lost), _f32(oe), _f32(oa))
+    if rc != 0:
+        raise ValueError("key out of range")
+    return oe, oa
 
 
 def update(E, A, PE, PA, k: int, S: int, lr: float, eps: float, keys, grads,

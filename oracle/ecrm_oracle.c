@@ -107,6 +107,90 @@ void ecrm_oracle_decode_member(const float *T, const float *P, uint64_t R, uint3
         }
 }
 
+/* ---- loss of one server (Sec. 3.4): every unit it held is rebuilt from the k other units of its
+ *      stripe -- a lost entry by the subtraction decoder, a lost parity by re-encoding.  The k+1
+ *      units of a stripe are on k+1 different servers, so a stripe loses at most one unit. ------- */
+
+static void rebuild_unit(float *T, float *P, uint64_t g, uint32_t D, uint32_t k, uint32_t lost /* k = parity */)
+{
+    for (uint32_t d = 0; d < D; ++d) {
+        if (lost == k) {
+            double p = 0.0;
+            for (uint32_t j = 0; j < k; ++j) p += (double)T[(g * k + j) * D + d];
+            P[g * D + d] = (float)p;
+        } else {
+            double e = (double)P[g * D + d];
+            for (uint32_t j = 0; j < k; ++j)
+                if (j != lost) e -= (double)T[(g * k + j) * D + d];
+            T[(g * k + lost) * D + d] = (float)e;
+        }
+    }
+}
+
+/* which unit of stripe g lives on `server`: -1 none, k the parity, j < k member j */
+static int unit_held(uint64_t g, uint32_t k, uint32_t S, uint32_t server)
+{
+    if (parity_server_of(g, S) == server) return (int)k;
+    for (uint32_t j = 0; j < k; ++j)
+        if (data_server_of(g, j, S) == server) return (int)j;
+    return -1;
+}
+
+int ecrm_oracle_recover_server(float *E, float *A, float *PE, float *PA, uint64_t R, uint32_t D, uint32_t k,
+                               uint32_t S, uint32_t server)
+{
+    if (server >= S) return -1;
+    for (uint64_t g = 0; g < R / k; ++g) {
+        const int u = unit_held(g, k, S, server);
+        if (u < 0) continue;
+        rebuild_unit(E, PE, g, D, k, (uint32_t)u);
+        rebuild_unit(A, PA, g, D, k, (uint32_t)u);
+    }
+    return 0;
+}
+
+/* marks with NaN what the server held (the test's way of losing a server) */
+int ecrm_oracle_fail_server(float *E, float *A, float *PE, float *PA, uint64_t R, uint32_t D, uint32_t k,
+                            uint32_t S, uint32_t server)
+{
+    if (server >= S) return -1;
+    for (uint64_t g = 0; g < R / k; ++g) {
+        const int u = unit_held(g, k, S, server);
+        if (u < 0) continue;
+        float *e = u == (int)k ? PE + g * D : E + (g * k + u) * D;
+        float *a = u == (int)k ? PA + g * D : A + (g * k + u) * D;
+        for (uint32_t d = 0; d < D; ++d) { e[d] = NAN; a[d] = NAN; }
+    }
+    return 0;
+}
+
+/* Degraded read (Sec. 3.4): entries of the keys while `lost` is down (lost >= S: nobody is down) */
+int ecrm_oracle_degraded_read(const float *E, const float *A, const float *PE, const float *PA, uint64_t R,
+                              uint32_t D, uint32_t k, uint32_t S, const uint64_t *keys, uint64_t n, uint32_t lost,
+                              float *out_E, float *out_A)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        const uint64_t x = keys[i];
+        if (x >= R) return -1;
+        const uint64_t g = stripe_of(x, k);
+        const uint32_t j = member_of(x, k);
+        const int down = lost < S && data_server_of(g, j, S) == lost;
+        for (uint32_t d = 0; d < D; ++d) {
+            if (!down) {
+                out_E[i * D + d] = E[x * D + d];
+                out_A[i * D + d] = A[x * D + d];
+            } else {
+                double e = (double)PE[g * D + d], a = (double)PA[g * D + d];
+                for (uint32_t m = 0; m < k; ++m)
+                    if (m != j) { e -= (double)E[(g * k + m) * D + d]; a -= (double)A[(g * k + m) * D + d]; }
+                out_E[i * D + d] = (float)e;
+                out_A[i * D + d] = (float)a;
+            }
+        }
+    }
+    return 0;
+}
+
 /* ---- the update path: Adagrad on the entry (Sec. 3.3.1), then the differences in entry and
  *      optimizer state are added to the parity entry and parity accumulator (Sec. 3.3.2) ----- */
 

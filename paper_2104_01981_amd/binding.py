@@ -18,7 +18,8 @@ _lib = None
 
 SYMBOLS = ["ecrm_create", "ecrm_destroy", "ecrm_data_bytes", "ecrm_parity_bytes", "ecrm_scratch_bytes",
            "ecrm_bind", "ecrm_encode", "ecrm_route", "ecrm_update", "ecrm_status", "ecrm_clear_status",
-           "ecrm_profile", "ecrm_profile_read", "ecrm_batch_stats", "ecrm_strerror"]
+           "ecrm_profile", "ecrm_profile_read", "ecrm_batch_stats", "ecrm_strerror",
+           "ecrm_fail_server", "ecrm_recover_server", "ecrm_degraded_read"]
 
 
 class EcrmConfig(C.Structure):
@@ -54,6 +55,9 @@ def load_library():
         lib.ecrm_encode.argtypes = [vp, vp]
         lib.ecrm_route.argtypes = [vp, u64p, C.c_uint64, u64p, u32p, u32p, u32p, vp]
         lib.ecrm_update.argtypes = [vp, u64p, f32p, C.c_uint64, vp]
+        lib.ecrm_fail_server.argtypes = [vp, C.c_uint32, vp]
+        lib.ecrm_recover_server.argtypes = [vp, C.c_uint32, vp]
+        lib.ecrm_degraded_read.argtypes = [vp, u64p, C.c_uint64, C.c_uint32, f32p, f32p, vp]
         lib.ecrm_status.argtypes = [vp, vp]
         lib.ecrm_clear_status.argtypes = [vp, vp]
         lib.ecrm_profile.argtypes = [vp, C.c_int]
@@ -147,6 +151,24 @@ class Ecrm:
         rc = self._lib.ecrm_update(self._ctx, _ptr(keys), _ptr(grads), C.c_uint64(n), _stream(stream))
         if check and rc != ECRM_OK:
             raise EcrmError(rc, "ecrm_update")
+        return rc
+
+    def fail_server(self, server, stream=None):
+        rc = self._lib.ecrm_fail_server(self._ctx, C.c_uint32(server), _stream(stream))
+        if rc != ECRM_OK:
+            raise EcrmError(rc, "ecrm_fail_server")
+
+    def recover_server(self, server, stream=None):
+        rc = self._lib.ecrm_recover_server(self._ctx, C.c_uint32(server), _stream(stream))
+        if rc != ECRM_OK:
+            raise EcrmError(rc, "ecrm_recover_server")
+
+    def degraded_read(self, keys, lost_server, out_E, out_A=None, stream=None, check=True):
+        lost = 0xFFFFFFFF if lost_server is None else lost_server
+        rc = self._lib.ecrm_degraded_read(self._ctx, _ptr(keys), C.c_uint64(keys.numel()), C.c_uint32(lost),
+                                          _ptr(out_E), _ptr(out_A), _stream(stream))
+        if check and rc != ECRM_OK:
+            raise EcrmError(rc, "ecrm_degraded_read")
         return rc
 
     def status(self, stream=None):

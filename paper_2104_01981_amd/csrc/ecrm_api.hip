@@ -219,6 +219,38 @@ int ecrm_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uint64_t 
     return check_launch();
 }
 
+int ecrm_fail_server(ecrm_ctx *c, uint32_t server, void *stream)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!c->bound) return ECRM_ENOTBOUND;
+    if (server >= c->geo.S) return ECRM_EINVAL;
+    launch_fail_server(c->geo, c->E, c->A, c->PE, c->PA, server, c->grid_blocks, (hipStream_t)stream);
+    return check_launch();
+}
+
+int ecrm_recover_server(ecrm_ctx *c, uint32_t server, void *stream)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!c->bound) return ECRM_ENOTBOUND;
+    if (server >= c->geo.S) return ECRM_EINVAL;
+    launch_recover_server(c->geo, c->E, c->A, c->PE, c->PA, server, c->grid_blocks, (hipStream_t)stream);
+    return check_launch();
+}
+
+int ecrm_degraded_read(ecrm_ctx *c, const uint64_t *keys, uint64_t n, uint32_t lost_server, float *out_E,
+                       float *out_A, void *stream)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!c->bound) return ECRM_ENOTBOUND;
+    if (lost_server != ECRM_NO_SERVER && lost_server >= c->geo.S) return ECRM_EINVAL;
+    if (n == 0) return ECRM_OK;
+    if (!aligned(keys, 8) || !aligned(out_E, 16) || (out_A && !aligned(out_A, 16))) return ECRM_EINVAL;
+    init_if_needed(c, (hipStream_t)stream);
+    launch_degraded_read(c->s, c->geo, c->E, c->A, c->PE, c->PA, keys, n, lost_server, out_E, out_A,
+                         c->grid_blocks, (hipStream_t)stream);
+    return check_launch();
+}
+
 int ecrm_status(ecrm_ctx *c, void *stream)
 {
     if (!c) return ECRM_EINVAL;

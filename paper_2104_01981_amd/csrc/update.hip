@@ -428,6 +428,11 @@ __device__ __forceinline__ void apply_stripe_general(const ApplyArgs &a, uint32_
     }
 }
 
+#ifndef ECRM_PREFETCH
+#define ECRM_PREFETCH 1
+#endif
+constexpr int kPrefetch = ECRM_PREFETCH;   // entries whose loads are issued ahead of the one being computed
+
 // Loads of one entry's work: its row of E and A, its first gradient, and -- when it opens a
 // stripe -- the stripe's parity rows.
 template <int NC>
@@ -479,21 +484,32 @@ __device__ __forceinline__ void apply_window(const ApplyArgs &a, uint32_t wkey, 
     const uint32_t col0 = cb * NC * 128u;
     unsigned long long todo = rowheads & bits_below(end) & ~bits_below(first);
     if (!todo) return;
-    RowLoads<NC> nxt;
-    issue_row<NC>(nxt, a, col0, wkey, widx, stripeheads, lowest_bit(todo));
-    todo &= todo - 1ull;
+    RowLoads<NC> q[kPrefetch];                        // entries whose loads are in flight, in order
+    int qn = 0;
+#pragma unroll
+    for (int s = 0; s < kPrefetch; ++s) {
+        if (todo) {
+            issue_row<NC>(q[s], a, col0, wkey, widx, stripeheads, lowest_bit(todo));
+            todo &= todo - 1ull;
+            qn = s + 1;
+        }
+    }
     D2 pe[NC], pa[NC];
 #pragma unroll
     for (int i = 0; i < NC; ++i) pe[i] = pa[i] = D2{0, 0};
     while (true) {
-        const RowLoads<NC> cur = nxt;
-        const bool has_next = todo != 0ull;
-        uint32_t rend = end;
-        if (has_next) {
-            rend = lowest_bit(todo);
+        const RowLoads<NC> cur = q[0];
+#pragma unroll
+        for (int s = 0; s + 1 < kPrefetch; ++s) q[s] = q[s + 1];
+        --qn;
+        if (todo) {
+            issue_row<NC>(q[kPrefetch - 1], a, col0, wkey, widx, stripeheads, lowest_bit(todo));
             todo &= todo - 1ull;
-            issue_row<NC>(nxt, a, col0, wkey, widx, stripeheads, rend);
+            ++qn;                                     // the queue was full before the pop: slot kPrefetch-1 is free
         }
+        const bool has_next = qn > 0;
+        const uint32_t rend = has_next ? q[0].j : end;
+        const bool next_opens = has_next && q[0].opens;
         D2 G[NC], acc[NC];
         float2 gr[NC];
 #pragma unroll
@@ -537,7 +553,7 @@ __device__ __forceinline__ void apply_window(const ApplyArgs &a, uint32_t wkey, 
             pa[i].x += G[i].x - a64.x;
             pa[i].y += G[i].y - a64.y;
         }
-        if (!has_next || nxt.opens) {                 // last entry of its stripe: the parity rows are complete
+        if (!has_next || next_opens) {                // last entry of its stripe: the parity rows are complete
             const uint32_t g = cur.x / k;
             const rsrc_t perow = row_f32(a.PE, g, D, col0), parow = row_f32(a.PA, g, D, col0);
 #pragma unroll
