@@ -31,7 +31,7 @@ TRAFFIC_SOURCES = ["paper_2104_01981_amd/csrc/update.hip", "paper_2104_01981_amd
 TRAFFIC_SOURCES_SHA256 = "7e090d60a1a77ae5048b7ca60372aaef0ee74d4d59cd040e35be52afee369f61"
 
 
-def measured_traffic(workload, scale_shift):
+def measured_traffic(workload, scale_shift, variant=""):
     import hashlib
     h = hashlib.sha256()
     try:
@@ -39,7 +39,7 @@ def measured_traffic(workload, scale_shift):
             h.update(open(os.path.join(ROOT, rel), "rb").read())
     except OSError:
         return None
-    if workload != "hbm_scale" or scale_shift or h.hexdigest() != TRAFFIC_SOURCES_SHA256:
+    if workload != "hbm_scale" or scale_shift or variant or h.hexdigest() != TRAFFIC_SOURCES_SHA256:
         return None
     return TRAFFIC_BYTES_PER_LAUNCH
 
@@ -55,6 +55,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="hbm_scale")
     ap.add_argument("--scale-shift", type=int, default=0, help="halve n and R this many times (debugging)")
+    ap.add_argument("--dim", type=int, default=0, help="floats per entry (default: the workload's 128)")
+    ap.add_argument("--k", type=int, default=0, help="entries per parity (default 4)")
+    ap.add_argument("--servers", type=int, default=0, help="servers (default 5)")
+    ap.add_argument("--optimizer", default="adagrad", choices=["adagrad", "momentum"])
+    ap.add_argument("--combine", action="store_true", help="synchronous variant: one update per modified entry")
+    ap.add_argument("--resident", type=int, default=0, help="batches kept resident and cycled through (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-recovery", action="store_true", help="skip the recovery-decode measurement")
     ap.add_argument("--layout", default="arena", choices=["arena", "arena-rev", "arena-spread", "separate"])
@@ -97,13 +103,22 @@ def main():
         return
     w = si.WORKLOADS[args.workload]
     sh = args.scale_shift
-    R, D, k, S = w["R"] >> sh, si.DEFAULT_D, si.DEFAULT_K, si.DEFAULT_S
-    nb = w["batches"]
-    per = (w["n"] >> sh) // nb
+    D, k, S = args.dim or si.DEFAULT_D, args.k or si.DEFAULT_K, args.servers or si.DEFAULT_S
+    R_gen = w["R"] >> sh                      # the key generators' row count (a power of two)
+    R = R_gen // k * k                        # rows of the tables: the largest multiple of k below it
+    per = (w["n"] >> sh) // w["batches"]
+    nb = min(w["batches"], args.resident) if args.resident else w["batches"]
     seed = w["seed"]
+    variant = "".join(f"/{n_}{v}" for n_, v, d in (("D", D, si.DEFAULT_D), ("k", k, si.DEFAULT_K), ("S", S, si.DEFAULT_S))
+                      if v != d)
+    if args.optimizer != "adagrad":
+        variant += "/momentum0.9"
+    if args.combine:
+        variant += "/combined"
 
     t_setup = time.perf_counter()
-    ctx = Ecrm(R, D, k, S, si.DEFAULT_LR, si.DEFAULT_EPS, per)
+    ctx = Ecrm(R, D, k, S, si.DEFAULT_LR, si.DEFAULT_EPS, per, optimizer=1 if args.optimizer == "momentum" else 0,
+               momentum=0.9 if args.optimizer == "momentum" else 0.0, combine=1 if args.combine else 0)
     # one arena for everything that stays resident (tables, scratch, all batches), carved at 2 MiB
     ALIGN = 2 << 20
     sizes = {"E": R * D * 4, "A": R * D * 4, "PE": R // k * D * 4, "PA": R // k * D * 4, "ld": S * 8, "lp": S * 8,
@@ -176,7 +191,8 @@ def main():
     keys, grads, alg_path, alg_apply = [], [], [], []
     for b in range(nb):
         kt = carve(f"keys{b}", torch.int64, (per,))
-        kt.copy_(si.workload_keys_t(args.workload, b, sh, dev))
+        kg = si.workload_keys_t(args.workload, b, sh, dev)
+        kt.copy_(torch.where(kg >= R, kg - R, kg))          # only differs when k does not divide 2^m
         keys.append(kt)
         gt = carve(f"grads{b}", torch.float32, (per, D))
         for i0 in range(0, per, CH):
@@ -240,12 +256,12 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}" + (f">>{sh}" if sh else ""), "items_per_step": per,
-                   "rows": R, "dim": D, "k": k, "servers": S, "storage": "f32", "optimizer": "adagrad",
+        "config": {"workload": f"{args.workload}" + (f">>{sh}" if sh else "") + variant, "items_per_step": per,
+                   "rows": R, "dim": D, "k": k, "servers": S, "storage": "f32", "optimizer": args.optimizer, "combine": bool(args.combine),
                    "keys": w["kind"], "batches_resident": nb},
-        "roofline": {"bound": "hbm", "kernel": "apply_stripes_kernel_d128", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "apply_stripes_kernel_d128" if D <= 128 else "apply_stripes_kernel_d256", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic(args.workload, sh),
+                     "traffic": measured_traffic(args.workload, sh, variant),
                      "algorithmic_bytes_per_launch": apply_bytes, "avg_launch_ms": apply_ms},
         "phases_ms_per_step": {"group": ms[0] / calls, "chains": ms[1] / calls, "apply": apply_ms},
         "path": {"algorithmic_bytes_per_step": path_bytes, "achieved_GBps": path_gbs,

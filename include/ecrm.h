@@ -43,17 +43,26 @@ enum {
     ECRM_EHIP = -6       /* a HIP runtime call failed                                      */
 };
 
-enum { ECRM_OPT_ADAGRAD = 0 };
+enum { ECRM_OPT_ADAGRAD = 0, ECRM_OPT_MOMENTUM = 1 };
 
 typedef struct {
     uint64_t rows;      /* R: k <= R <= 2^32 - 4096, multiple of k                              */
     uint32_t dim;       /* D: floats per entry, multiple of 4, 4..1024 (the paper uses 128, 256) */
     uint32_t k;         /* data entries per parity, 1..64 (paper: 2, 4, 10); r is fixed to 1     */
     uint32_t servers;   /* S: k+1 <= S <= 1024 (paper: 5)                                        */
-    uint32_t optimizer; /* ECRM_OPT_ADAGRAD: the update rule printed in Sec. 3.3.1               */
+    uint32_t optimizer; /* ECRM_OPT_ADAGRAD: the update rule printed in Sec. 3.3.1;
+                           ECRM_OPT_MOMENTUM: SGD with momentum, the optimizer of the paper's evaluation
+                           (Sec. 4.1; the paper prints no formula): v <- momentum*v + g, e <- e - lr*v,
+                           with A holding v                                                       */
     float lr;           /* learning rate, used as its exact fp32 value                           */
     float eps;          /* Adagrad epsilon (under the square root), >= 0                         */
     uint64_t max_batch; /* largest n ever passed to ecrm_update, 1 .. 2^31 (sizes the scratch)   */
+    float momentum;     /* ECRM_OPT_MOMENTUM only: coefficient in [0, 1)                          */
+    uint32_t combine;   /* 0: several updates to one entry inside a call are applied one after the
+                           other in arrival order (asynchronous training, Sec. 2.1).
+                           1: their gradients are summed and applied as ONE update per modified entry,
+                           and the load counters count one update per modified entry (the synchronous
+                           variant of Sec. 4.4 "Synchronous training")                             */
 } ecrm_config;
 
 /* Validates the configuration and creates a host-side context.  No device memory is touched. */

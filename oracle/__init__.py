@@ -35,6 +35,7 @@ def lib():
         _lib.ecrm_oracle_load.restype = C.c_int
         _lib.ecrm_oracle_max_threads.restype = C.c_int
         _lib.ecrm_oracle_recover_server.restype = C.c_int
+        _lib.ecrm_oracle_update_rule.restype = C.c_int
         _lib.ecrm_oracle_fail_server.restype = C.c_int
         _lib.ecrm_oracle_degraded_read.restype = C.c_int
     return _lib
@@ -139,6 +140,24 @@ def update(E, A, PE, PA, k: int, S: int, lr: float, eps: float, keys, grads,
         raise ValueError("key out of range")
     if rc != 0:
         raise RuntimeError(f"oracle update failed ({rc})")
+
+
+def update_rule(E, A, PE, PA, k: int, S: int, lr: float, eps: float, momentum: float, optimizer: int,
+                combine: int, keys, grads, load_data=None, load_parity=None) -> None:
+    """Adagrad (0) or momentum SGD (1), updates applied one by one (combine 0) or summed per entry (1)."""
+    R, D = E.shape
+    n = len(keys)
+    assert grads.shape == (n, D)
+    ld = _u64(load_data) if load_data is not None else None
+    lp = _u64(load_parity) if load_parity is not None else None
+    rc = lib().ecrm_oracle_update_rule(_f32(E), _f32(A), _f32(PE), _f32(PA), C.c_uint64(R), C.c_uint32(D),
+                                       C.c_uint32(k), C.c_uint32(S), C.c_float(lr), C.c_float(eps),
+                                       C.c_float(momentum), C.c_uint32(optimizer), C.c_uint32(combine),
+                                       _u64(keys), _f32(grads), C.c_uint64(n), ld, lp)
+    if rc == -1:
+        raise ValueError("key out of range")
+    if rc != 0:
+        raise RuntimeError(f"oracle update_rule failed ({rc})")
 
 
 def update_gradient_propagation(E, A, PE, PA, k: int, lr: float, eps: float, keys, grads) -> None:

@@ -295,6 +295,86 @@ int ecrm_oracle_update_gradient_propagation(float *E, float *A, float *PE, float
     return 0;
 }
 
+/*
+ * The other update rules.  optimizer 0 = Adagrad (Sec. 3.3.1); optimizer 1 = SGD with momentum, the
+ * optimizer of the paper's evaluation (Sec. 4.1), for which the paper prints no formula: taken as
+ *     v <- mu * v + g ;  e <- e - lr * v          (A holds v, one state float per parameter).
+ * combine 0 = every update applied on its own, in arrival order (asynchronous training);
+ * combine 1 = the synchronous variant of Sec. 4.4: the gradients an entry receives in the call are
+ *             added up (in arrival order) and ONE update is applied per modified entry; the load
+ *             counters then count one entry update and one parity update per modified entry.
+ * In every case the differences in entry and state are added to the stripe's parity rows
+ * (Sec. 3.3.2).  Single-threaded on purpose.  Parity unpinned by the paper: the momentum formula.
+ */
+static void rule_step(double *e, double *a, double g, uint32_t optimizer, double lr, double eps, double mu)
+{
+    if (optimizer == 0) {
+        *a = *a + g * g;
+        *e = *e - lr / sqrt(*a + eps) * g;
+    } else {
+        *a = mu * *a + g;
+        *e = *e - lr * *a;
+    }
+}
+
+int ecrm_oracle_update_rule(float *E, float *A, float *PE, float *PA,
+                            uint64_t R, uint32_t D, uint32_t k, uint32_t S, float lr_f, float eps_f, float mu_f,
+                            uint32_t optimizer, uint32_t combine,
+                            const uint64_t *keys, const float *grads, uint64_t n,
+                            uint64_t *load_data, uint64_t *load_parity)
+{
+    if (k == 0 || R % k != 0 || S < k + 1 || optimizer > 1 || combine > 1) return -3;
+    for (uint64_t i = 0; i < n; ++i)
+        if (keys[i] >= R) return -1;
+    const double lr = (double)lr_f, eps = (double)eps_f, mu = (double)mu_f;
+    const uint64_t Gn = R / k;
+    double *E64 = widen(E, R * D), *A64 = widen(A, R * D);
+    double *PE64 = widen(PE, Gn * D), *PA64 = widen(PA, Gn * D);
+    double *sum = combine ? (double *)calloc(R * D, sizeof(double)) : NULL;
+    unsigned char *hit = combine ? (unsigned char *)calloc(R, 1) : NULL;
+    if (!E64 || !A64 || !PE64 || !PA64 || (combine && (!sum || !hit))) {
+        free(E64); free(A64); free(PE64); free(PA64); free(sum); free(hit);
+        return -2;
+    }
+    if (!combine) {
+        for (uint64_t i = 0; i < n; ++i) {
+            const uint64_t x = keys[i], g = stripe_of(x, k);
+            for (uint32_t d = 0; d < D; ++d) {
+                double *e = &E64[x * D + d], *a = &A64[x * D + d];
+                const double e_old = *e, a_old = *a;
+                rule_step(e, a, (double)grads[i * D + d], optimizer, lr, eps, mu);
+                PE64[g * D + d] += *e - e_old;
+                PA64[g * D + d] += *a - a_old;
+            }
+            if (load_data) load_data[data_server_of(g, member_of(x, k), S)] += 1;
+            if (load_parity) load_parity[parity_server_of(g, S)] += 1;
+        }
+    } else {
+        for (uint64_t i = 0; i < n; ++i) {
+            const uint64_t x = keys[i];
+            hit[x] = 1;
+            for (uint32_t d = 0; d < D; ++d) sum[x * D + d] += (double)grads[i * D + d];
+        }
+        for (uint64_t x = 0; x < R; ++x) {
+            if (!hit[x]) continue;
+            const uint64_t g = stripe_of(x, k);
+            for (uint32_t d = 0; d < D; ++d) {
+                double *e = &E64[x * D + d], *a = &A64[x * D + d];
+                const double e_old = *e, a_old = *a;
+                rule_step(e, a, sum[x * D + d], optimizer, lr, eps, mu);
+                PE64[g * D + d] += *e - e_old;
+                PA64[g * D + d] += *a - a_old;
+            }
+            if (load_data) load_data[data_server_of(g, member_of(x, k), S)] += 1;
+            if (load_parity) load_parity[parity_server_of(g, S)] += 1;
+        }
+    }
+    narrow(E, E64, R * D);   narrow(A, A64, R * D);
+    narrow(PE, PE64, Gn * D); narrow(PA, PA64, Gn * D);
+    free(E64); free(A64); free(PE64); free(PA64); free(sum); free(hit);
+    return 0;
+}
+
 int ecrm_oracle_max_threads(void)
 {
 #ifdef _OPENMP

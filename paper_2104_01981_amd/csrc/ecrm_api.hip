@@ -74,8 +74,10 @@ int ecrm_create(const ecrm_config *cfg, ecrm_ctx **out)
     if (cfg->rows < cfg->k || cfg->rows % cfg->k != 0 || cfg->rows > 0xFFFFFFFFull - 4096) return ECRM_EINVAL;
     if (cfg->dim < 4 || cfg->dim > 1024 || cfg->dim % 4 != 0) return ECRM_EINVAL;
     if (cfg->servers < cfg->k + 1 || cfg->servers > 1024) return ECRM_EINVAL;
-    if (cfg->optimizer != ECRM_OPT_ADAGRAD) return ECRM_EINVAL;
+    if (cfg->optimizer != ECRM_OPT_ADAGRAD && cfg->optimizer != ECRM_OPT_MOMENTUM) return ECRM_EINVAL;
+    if (cfg->combine > 1) return ECRM_EINVAL;
     if (!isfinite(cfg->lr) || !isfinite(cfg->eps) || cfg->eps < 0.0f) return ECRM_EINVAL;
+    if (cfg->optimizer == ECRM_OPT_MOMENTUM && !(cfg->momentum >= 0.0f && cfg->momentum < 1.0f)) return ECRM_EINVAL;
     if (cfg->max_batch < 1 || cfg->max_batch > (1ull << 31)) return ECRM_EINVAL;
 
     ecrm_ctx *c = new (std::nothrow) ecrm_ctx;
@@ -90,6 +92,8 @@ int ecrm_create(const ecrm_config *cfg, ecrm_ctx **out)
     c->geo.ncb = (cfg->dim + c->geo.nc * 128 - 1) / (c->geo.nc * 128);
     c->geo.lr = cfg->lr;
     c->geo.eps = cfg->eps;
+    c->geo.mu = cfg->optimizer == ECRM_OPT_MOMENTUM ? cfg->momentum : 0.0f;
+    c->geo.mode = cfg->optimizer + 2u * cfg->combine;
     c->key_bits = 1;
     while (c->key_bits < 32 && (1ull << c->key_bits) < cfg->rows) ++c->key_bits;
     c->max_batch = (uint32_t)cfg->max_batch;

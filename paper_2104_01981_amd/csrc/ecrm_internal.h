@@ -57,6 +57,8 @@ struct Geometry {
     uint32_t nc;           // 128-float chunks a lane holds at once (1 or 2)
     uint32_t ncb;          // column blocks of nc*128 floats that cover D
     float lr, eps;
+    float mu;              // momentum coefficient (momentum SGD only)
+    uint32_t mode;         // optimizer + 2 * combine: which update rule the kernels are instantiated for
 };
 
 // ---- launchers (each checks nothing: the API layer validates shapes before calling) -------------

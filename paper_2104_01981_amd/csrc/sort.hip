@@ -90,7 +90,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
                 key = (uint32_t)k64;
                 if (k64 >= (uint64_t)rows) {
                     bad = true;
-                } else {
+                } else if (S) {                                   // S == 0: the caller counts per distinct row later
                     const uint32_t g = key / k, j = key - g * k;
                     atomicAdd(&s_cnt[(g + 1 + j) % S], 1u);       // server of the entry
                     atomicAdd(&s_cnt[S + g % S], 1u);             // server of its parity
@@ -260,7 +260,7 @@ void launch_sort(const Scratch &s, const Geometry &g, const uint64_t *keys, uint
         if (p == 0) {
             hipLaunchKernelGGL(sort_hist_kernel<true>, dim3(nblocks), dim3(kSortThreads), 0, st,
                                (const void *)keys, n, nblocks, shift, bits, s.block_hist, s.hdr, s.cnt,
-                               g.rows, g.k, g.S);
+                               g.rows, g.k, (g.mode & 2u) ? 0u : g.S);
             hipLaunchKernelGGL(sort_scan_kernel, dim3(bins), dim3(kSortThreads), 0, st, s.block_hist,
                                s.bin_total, nblocks);
             hipLaunchKernelGGL(sort_scatter_kernel<true>, dim3(nblocks), dim3(kSortThreads), 0, st,

@@ -76,15 +76,83 @@ __device__ __forceinline__ void std2(rsrc_t r, int i, D2 d)
 }
 __device__ __forceinline__ D2 widen2(float2 f) { return D2{(double)f.x, (double)f.y}; }
 __device__ __forceinline__ float2 narrow2(D2 d) { return float2{(float)d.x, (float)d.y}; }
-__device__ __forceinline__ void step2(D2 &G, D2 &acc, float2 g, double lr, double eps)
+
+// ---- update rules --------------------------------------------------------------------------------
+// MODE = optimizer + how several updates to one entry inside a call are treated:
+//   sequential: applied one after the other in arrival order (asynchronous training, Sec. 2.1, 3.3.2);
+//   combined:   their gradients are summed and applied as ONE update (the synchronous variant sketched
+//               in Sec. 4.4 "Synchronous training").
+// Adagrad is the rule printed in Sec. 3.3.1.  Momentum SGD (the optimizer of the paper's evaluation,
+// Sec. 4.1, which gives no formula) is taken as v <- mu*v + g, e <- e - lr*v, one state float per
+// parameter.  For every rule a chain keeps a running value s and the sum acc of the steps taken; the
+// entry moves by -acc and its state becomes s.
+enum { kAdagradSeq = 0, kMomentumSeq = 1, kAdagradCombine = 2, kMomentumCombine = 3 };
+struct RuleParams { double lr, eps, mu; };
+
+template <int MODE>
+struct Rule {
+    static constexpr bool combine = MODE == kAdagradCombine || MODE == kMomentumCombine;
+    static __device__ __forceinline__ double start(double state0) { return combine ? 0.0 : state0; }
+    // one update g of the chain
+    static __device__ __forceinline__ void item(double &s, double &acc, float gf, const RuleParams &p)
+    {
+        if (MODE == kAdagradSeq) adagrad_step(s, acc, gf, p.lr, p.eps);
+        else if (MODE == kMomentumSeq) { s = fma(p.mu, s, (double)gf); acc = fma(p.lr, s, acc); }
+        else s += (double)gf;
+    }
+    // what a piece of a long chain contributes when started from zero (phase 1 of the split chain)
+    static __device__ __forceinline__ void summary(double &s, float gf, const RuleParams &p)
+    {
+        if (MODE == kAdagradSeq) s = fma((double)gf, (double)gf, s);
+        else if (MODE == kMomentumSeq) s = fma(p.mu, s, (double)gf);
+        else s += (double)gf;
+    }
+    // end of the chain: the combined rules take their single step here
+    static __device__ __forceinline__ void finish(double &s, double &acc, double state0, const RuleParams &p)
+    {
+        if (MODE == kAdagradCombine) {
+            const double g = s;
+            double G = state0, a = 0.0;
+            // one Adagrad step with the summed gradient (g is not an fp32 value: inline the step)
+            G = fma(g, g, G);
+            const double x = G + p.eps;
+            double y = (double)__builtin_amdgcn_rsqf((float)x);
+            const double h = 0.5 * x * y;
+            y = fma(y, fma(-h, y, 0.5), y);
+            a = p.lr * g * y;
+            s = G;
+            acc = a;
+        } else if (MODE == kMomentumCombine) {
+            const double v = fma(p.mu, state0, s);
+            s = v;
+            acc = p.lr * v;
+        }
+    }
+};
+
+template <int MODE>
+__device__ __forceinline__ void item2(D2 &s, D2 &acc, float2 g, const RuleParams &p)
 {
-    adagrad_step(G.x, acc.x, g.x, lr, eps);
-    adagrad_step(G.y, acc.y, g.y, lr, eps);
+    Rule<MODE>::item(s.x, acc.x, g.x, p);
+    Rule<MODE>::item(s.y, acc.y, g.y, p);
 }
-__device__ __forceinline__ void sumsq2(D2 &s, float2 g)
+template <int MODE>
+__device__ __forceinline__ void summary2(D2 &s, float2 g, const RuleParams &p)
 {
-    s.x = fma((double)g.x, (double)g.x, s.x);
-    s.y = fma((double)g.y, (double)g.y, s.y);
+    Rule<MODE>::summary(s.x, g.x, p);
+    Rule<MODE>::summary(s.y, g.y, p);
+}
+template <int MODE>
+__device__ __forceinline__ D2 start2(D2 state0) { return D2{Rule<MODE>::start(state0.x), Rule<MODE>::start(state0.y)}; }
+template <int MODE>
+__device__ __forceinline__ void finish2(D2 &s, D2 &acc, D2 state0, const RuleParams &p)
+{
+    Rule<MODE>::finish(s.x, acc.x, state0.x, p);
+    Rule<MODE>::finish(s.y, acc.y, state0.y, p);
+}
+__device__ __forceinline__ RuleParams rule_params(const Geometry &g)
+{
+    return RuleParams{(double)g.lr, (double)g.eps, (double)g.mu};
 }
 
 __device__ __forceinline__ uint32_t wave_id() { return (blockIdx.x * blockDim.x + threadIdx.x) / kWave; }
@@ -157,12 +225,13 @@ __global__ __launch_bounds__(256) void long_plan_kernel(const uint32_t *sk, uint
     }
 }
 
-// Phase 1 (STEPS == false): partial[piece] = sum of g^2 over the piece.
-// Phase 3 (STEPS == true):  partial[piece] holds the piece's starting accumulator on entry and the
-//                           sum of its steps lr * g_t / sqrt(G_t + eps) on exit.
+// Phase 1 (STEPS == false): partial[piece] = the piece's summary started from zero (Adagrad: sum of
+//                           g^2; momentum: the velocity it builds; combined rules: sum of g).
+// Phase 3 (STEPS == true):  partial[piece] holds the piece's starting state on entry and the sum of
+//                           its steps on exit (sequential rules only).
 // One wave per piece; the item indices of 64 positions are fetched with one coalesced load and
 // handed out lane by lane, and U gradient rows are in flight at a time.
-template <int NC, bool STEPS>
+template <int NC, bool STEPS, int MODE>
 __global__ __launch_bounds__(256) void long_piece_kernel(const uint32_t *si, const float *grads, Header *hdr,
                                                          const uint32_t *long_head, const uint32_t *long_len,
                                                          const uint32_t *long_piece, const uint32_t *long_base,
@@ -172,7 +241,7 @@ __global__ __launch_bounds__(256) void long_piece_kernel(const uint32_t *si, con
     if (hdr->batch_bad) return;
     const uint32_t np = min(hdr->n_pieces, max_pieces);
     const uint32_t D = geo.D, lane = lane_id();
-    const double lr = (double)geo.lr, eps = (double)geo.eps;
+    const RuleParams rp = rule_params(geo);
     constexpr int U = 16;
     for (uint32_t pc = wave_id(); pc < np; pc += wave_count()) {
         const uint32_t slot = uniform(piece_slot[pc]);
@@ -210,8 +279,8 @@ __global__ __launch_bounds__(256) void long_piece_kernel(const uint32_t *si, con
                         if (u0 + u < cnt) {
 #pragma unroll
                             for (int i = 0; i < NC; ++i) {
-                                if (STEPS) step2(G[i], acc[i], g[u][i], lr, eps);
-                                else sumsq2(acc[i], g[u][i]);
+                                if (STEPS) item2<MODE>(G[i], acc[i], g[u][i], rp);
+                                else summary2<MODE>(acc[i], g[u][i], rp);
                             }
                         }
                     }
@@ -223,12 +292,15 @@ __global__ __launch_bounds__(256) void long_piece_kernel(const uint32_t *si, con
     }
 }
 
-// Phase 2: exclusive scan of the pieces' sums of squares, seeded with the stored accumulator;
-// long_res[slot][1] receives the accumulator after the whole run.  One wave per long row.
-template <int NC>
+// Phase 2: exclusive scan of the pieces' summaries, seeded with the stored state, so that every
+// piece knows the state it starts from: Adagrad adds the sums of squares; momentum composes
+// v -> mu^len * v + V_piece.  long_res[slot][1] receives the state after the whole run.
+// One wave per long row.
+template <int NC, int MODE>
 __global__ __launch_bounds__(256) void long_scan_kernel(const uint32_t *sk, const float *A, Header *hdr,
                                                         const uint32_t *long_head, const uint32_t *long_count,
-                                                        const uint32_t *long_base, double *partial,
+                                                        const uint32_t *long_base, const uint32_t *long_len,
+                                                        const uint32_t *long_piece, double *partial,
                                                         double *long_res, uint32_t max_slots, Geometry geo)
 {
     if (hdr->batch_bad) return;
@@ -238,6 +310,13 @@ __global__ __launch_bounds__(256) void long_scan_kernel(const uint32_t *sk, cons
     for (uint32_t slot = wave_id(); slot < nl; slot += wave_count()) {
         const uint32_t x = uniform(sk[long_head[slot]]);
         const uint32_t P = uniform(long_count[slot]), base = uniform(long_base[slot]);
+        // momentum: decay over a full piece and over the (shorter) last one
+        double decay_full = 1.0, decay_last = 1.0;
+        if (MODE == kMomentumSeq) {
+            const uint32_t C = uniform(long_piece[slot]), L = uniform(long_len[slot]);
+            decay_full = pow((double)geo.mu, (double)C);
+            decay_last = pow((double)geo.mu, (double)(L - (P - 1) * C));
+        }
         for (uint32_t cb = 0; cb < geo.ncb; ++cb) {
             const uint32_t col0 = cb * NC * 128u;
             const rsrc_t arow = row_f32(A, x, D, col0);
@@ -259,8 +338,14 @@ __global__ __launch_bounds__(256) void long_scan_kernel(const uint32_t *sk, cons
 #pragma unroll
                         for (int i = 0; i < NC; ++i) {
                             std2(r, i, G[i]);
-                            G[i].x += t[u][i].x;
-                            G[i].y += t[u][i].y;
+                            if (MODE == kMomentumSeq) {
+                                const double dec = j0 + u + 1 == P ? decay_last : decay_full;
+                                G[i].x = fma(dec, G[i].x, t[u][i].x);
+                                G[i].y = fma(dec, G[i].y, t[u][i].y);
+                            } else {
+                                G[i].x += t[u][i].x;
+                                G[i].y += t[u][i].y;
+                            }
                         }
                     }
                 }
@@ -335,11 +420,11 @@ struct ApplyArgs {
 // General path: the stripe whose first item sits at sorted position `pos` (wave-uniform), walked
 // through memory.  Used when the stripe does not fit the wave's window: runs of more than a few
 // dozen updates, and entries whose totals come from the split-chain path.
-template <int NC>
+template <int NC, int MODE>
 __device__ __forceinline__ void apply_stripe_general(const ApplyArgs &a, uint32_t pos, uint32_t cb)
 {
     const uint32_t D = a.geo.D, k = a.geo.k, n = a.n;
-    const double lr = (double)a.geo.lr, eps = (double)a.geo.eps;
+    const RuleParams rp = rule_params(a.geo);
     const uint32_t col0 = cb * NC * 128u;
     uint32_t key = uniform(a.sk[pos]);
     const uint32_t g = key / k;
@@ -369,14 +454,19 @@ __device__ __forceinline__ void apply_stripe_general(const ApplyArgs &a, uint32_
             const rsrc_t r1 = row_f64(a.long_res, (size_t)slot * 2 + 1, D, col0);
 #pragma unroll
             for (int i = 0; i < NC; ++i) {
-                acc[i] = ldd2(r0, i);
-                G[i] = ldd2(r1, i);
+                if (Rule<MODE>::combine) {           // slot 0 holds the sum of the run's gradients
+                    G[i] = ldd2(r0, i);
+                    acc[i] = D2{0, 0};
+                } else {                             // slot 0: sum of the steps, slot 1: state after the run
+                    acc[i] = ldd2(r0, i);
+                    G[i] = ldd2(r1, i);
+                }
             }
             cur += uniform(a.long_len[slot]);
         } else {
 #pragma unroll
             for (int i = 0; i < NC; ++i) {
-                G[i] = widen2(a0[i]);
+                G[i] = start2<MODE>(widen2(a0[i]));
                 acc[i] = D2{0, 0};
             }
             // the run is at most kLongRun long: walk it 64 positions at a time, U gradients in flight
@@ -402,7 +492,7 @@ __device__ __forceinline__ void apply_stripe_general(const ApplyArgs &a, uint32_
                     for (int u = 0; u < U; ++u)
                         if (u0 + u < cnt) {
 #pragma unroll
-                            for (int i = 0; i < NC; ++i) step2(G[i], acc[i], gr[u][i], lr, eps);
+                            for (int i = 0; i < NC; ++i) item2<MODE>(G[i], acc[i], gr[u][i], rp);
                         }
                 }
                 cur += cnt;
@@ -411,6 +501,7 @@ __device__ __forceinline__ void apply_stripe_general(const ApplyArgs &a, uint32_
 #pragma unroll
         for (int i = 0; i < NC; ++i) {
             const D2 e64 = widen2(e[i]), a64 = widen2(a0[i]);
+            finish2<MODE>(G[i], acc[i], a64, rp);
             st2(erow, i, narrow2(D2{e64.x - acc[i].x, e64.y - acc[i].y}));
             st2(arow, i, narrow2(G[i]));
             pe[i].x -= acc[i].x;
@@ -474,13 +565,13 @@ __device__ __forceinline__ void issue_row(RowLoads<NC> &r, const ApplyArgs &a, u
 // Window path: every stripe that opens in the first kChunk lanes of the wave's 64-position window
 // and ends inside the window.  Entries are taken one after the other; the loads of the next entry
 // are issued before the current one is computed, so two entries' rows are in flight per wave.
-template <int NC>
+template <int NC, int MODE>
 __device__ __forceinline__ void apply_window(const ApplyArgs &a, uint32_t wkey, uint32_t widx,
                                              unsigned long long rowheads, unsigned long long stripeheads,
                                              uint32_t first, uint32_t end, uint32_t cb)
 {
     const uint32_t D = a.geo.D, k = a.geo.k;
-    const double lr = (double)a.geo.lr, eps = (double)a.geo.eps;
+    const RuleParams rp = rule_params(a.geo);
     const uint32_t col0 = cb * NC * 128u;
     unsigned long long todo = rowheads & bits_below(end) & ~bits_below(first);
     if (!todo) return;
@@ -514,7 +605,7 @@ __device__ __forceinline__ void apply_window(const ApplyArgs &a, uint32_t wkey, 
         float2 gr[NC];
 #pragma unroll
         for (int i = 0; i < NC; ++i) {
-            G[i] = widen2(cur.a[i]);
+            G[i] = start2<MODE>(widen2(cur.a[i]));
             acc[i] = D2{0, 0};
             gr[i] = cur.g[i];
         }
@@ -529,7 +620,7 @@ __device__ __forceinline__ void apply_window(const ApplyArgs &a, uint32_t wkey, 
                 for (int i = 0; i < NC; ++i) nx[i] = ldg2(r, i);
             }
 #pragma unroll
-            for (int i = 0; i < NC; ++i) step2(G[i], acc[i], gr[i], lr, eps);
+            for (int i = 0; i < NC; ++i) item2<MODE>(G[i], acc[i], gr[i], rp);
             if (!more) break;
 #pragma unroll
             for (int i = 0; i < NC; ++i) gr[i] = nx[i];
@@ -546,6 +637,7 @@ __device__ __forceinline__ void apply_window(const ApplyArgs &a, uint32_t wkey, 
 #pragma unroll
         for (int i = 0; i < NC; ++i) {
             const D2 e64 = widen2(cur.e[i]), a64 = widen2(cur.a[i]);
+            finish2<MODE>(G[i], acc[i], a64, rp);
             st2(erow, i, narrow2(D2{e64.x - acc[i].x, e64.y - acc[i].y}));
             st2(arow, i, narrow2(G[i]));
             pe[i].x -= acc[i].x;
@@ -566,7 +658,7 @@ __device__ __forceinline__ void apply_window(const ApplyArgs &a, uint32_t wkey, 
     }
 }
 
-template <int NC>
+template <int NC, int MODE>
 __device__ __forceinline__ void apply_stripes_body(const ApplyArgs &a)
 {
     if (a.hdr->batch_bad) return;
@@ -601,24 +693,45 @@ __device__ __forceinline__ void apply_stripes_body(const ApplyArgs &a)
         const bool last_inside = after != 0ull || p0 + kWave >= n;
         const uint32_t end = last_inside ? (after ? lowest_bit(after) : vend) : last;
         for (uint32_t cb = 0; cb < a.geo.ncb; ++cb) {
-            apply_window<NC>(a, wkey, widx, rowheads, stripeheads, first, end, cb);
-            if (!last_inside) apply_stripe_general<NC>(a, p0 + last, cb);
+            apply_window<NC, MODE>(a, wkey, widx, rowheads, stripeheads, first, end, cb);
+            if (!last_inside) apply_stripe_general<NC, MODE>(a, p0 + last, cb);
         }
     }
 }
 
-#ifndef ECRM_APPLY_WAVES
-#define ECRM_APPLY_WAVES 1
-#endif
-// D <= 128
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ECRM_APPLY_WAVES, 8))) void apply_stripes_kernel_d128(ApplyArgs a)
+// D <= 128: one 128-float slice per lane pair; D > 128: two slices per lane.
+template <int MODE>
+__global__ __launch_bounds__(256) void apply_stripes_kernel_d128(ApplyArgs a)
 {
-    apply_stripes_body<1>(a);
+    apply_stripes_body<1, MODE>(a);
 }
-// D > 128: two 128-float slices per lane.
+template <int MODE>
 __global__ __launch_bounds__(256) void apply_stripes_kernel_d256(ApplyArgs a)
 {
-    apply_stripes_body<2>(a);
+    apply_stripes_body<2, MODE>(a);
+}
+
+// Combined (synchronous) rule: one update per modified entry, so the per-server load counts one per
+// distinct row of the batch and one parity update for each (Sec. 3.6, Sec. 4.4).
+__global__ __launch_bounds__(256) void count_rows_kernel(const uint32_t *sk, uint32_t n, Header *hdr,
+                                                         unsigned long long *cnt, uint32_t k, uint32_t S)
+{
+    __shared__ uint32_t s_cnt[2 * 1024];
+    if (hdr->batch_bad) return;
+    for (uint32_t i = threadIdx.x; i < 2 * S; i += blockDim.x) s_cnt[i] = 0;
+    __syncthreads();
+    const uint32_t stride = gridDim.x * blockDim.x;
+    for (uint32_t p = blockIdx.x * blockDim.x + threadIdx.x; p < n; p += stride) {
+        const uint32_t x = sk[p];
+        if (p == 0 || sk[p - 1] != x) {
+            const uint32_t g = x / k, j = x - g * k;
+            atomicAdd(&s_cnt[(g + 1 + j) % S], 1u);
+            atomicAdd(&s_cnt[S + g % S], 1u);
+        }
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < 2 * S; i += blockDim.x)
+        if (s_cnt[i]) atomicAdd(&cnt[i], (unsigned long long)s_cnt[i]);
 }
 
 // ================================================================================================
@@ -695,40 +808,76 @@ static int resident_grid(K kernel, int cus)
     return cus * per_cu;
 }
 
+template <int NC, int MODE>
+static void chains_for(const Scratch &s, const Geometry &g, const float *A, const float *grads,
+                       const uint32_t *sk, const uint32_t *si, uint32_t n, uint32_t max_slots,
+                       uint32_t max_pieces, int cus, hipStream_t st)
+{
+    static int grid_p1 = 0, grid_p3 = 0;
+    if (!grid_p1) {
+        grid_p1 = resident_grid(long_piece_kernel<NC, false, MODE>, cus);
+        grid_p3 = resident_grid(long_piece_kernel<NC, true, MODE>, cus);
+    }
+    const dim3 grid(cus * 8), block(256);
+    hipLaunchKernelGGL(long_find_kernel, grid, block, 0, st, sk, n, s.hdr, s.long_slot, s.long_head, max_slots);
+    hipLaunchKernelGGL(long_plan_kernel, grid, block, 0, st, sk, n, s.hdr, s.long_head, s.long_len, s.long_piece,
+                       s.long_count, s.long_base, s.piece_slot, max_slots, max_pieces);
+    hipLaunchKernelGGL((long_piece_kernel<NC, false, MODE>), dim3(grid_p1), block, 0, st, si, grads, s.hdr, s.long_head,
+                       s.long_len, s.long_piece, s.long_base, s.piece_slot, s.partial, max_pieces, g);
+    if (!Rule<MODE>::combine) {
+        hipLaunchKernelGGL((long_scan_kernel<NC, MODE>), grid, block, 0, st, sk, A, s.hdr, s.long_head, s.long_count,
+                           s.long_base, s.long_len, s.long_piece, s.partial, s.long_res, max_slots, g);
+        hipLaunchKernelGGL((long_piece_kernel<NC, true, MODE>), dim3(grid_p3), block, 0, st, si, grads, s.hdr,
+                           s.long_head, s.long_len, s.long_piece, s.long_base, s.piece_slot, s.partial, max_pieces, g);
+    }
+    hipLaunchKernelGGL((long_reduce_kernel<NC>), grid, block, 0, st, s.hdr, s.long_count, s.long_base, s.partial,
+                       s.long_res, max_slots, g);
+}
+
+template <int NC, int MODE>
+static void apply_for(const ApplyArgs &a, int cus, hipStream_t st)
+{
+    static int grid_apply = 0;
+    if (NC == 1) {
+        if (!grid_apply) grid_apply = resident_grid(apply_stripes_kernel_d128<MODE>, cus);
+        hipLaunchKernelGGL(apply_stripes_kernel_d128<MODE>, dim3(grid_apply), dim3(256), 0, st, a);
+    } else {
+        if (!grid_apply) grid_apply = resident_grid(apply_stripes_kernel_d256<MODE>, cus);
+        hipLaunchKernelGGL(apply_stripes_kernel_d256<MODE>, dim3(grid_apply), dim3(256), 0, st, a);
+    }
+}
+
+#define ECRM_DISPATCH(FN, ...)                                                   \
+    do {                                                                         \
+        if (g.nc == 1) {                                                         \
+            switch (g.mode) {                                                    \
+                case kAdagradSeq: FN<1, kAdagradSeq>(__VA_ARGS__); break;        \
+                case kMomentumSeq: FN<1, kMomentumSeq>(__VA_ARGS__); break;      \
+                case kAdagradCombine: FN<1, kAdagradCombine>(__VA_ARGS__); break; \
+                default: FN<1, kMomentumCombine>(__VA_ARGS__); break;            \
+            }                                                                    \
+        } else {                                                                 \
+            switch (g.mode) {                                                    \
+                case kAdagradSeq: FN<2, kAdagradSeq>(__VA_ARGS__); break;        \
+                case kMomentumSeq: FN<2, kMomentumSeq>(__VA_ARGS__); break;      \
+                case kAdagradCombine: FN<2, kAdagradCombine>(__VA_ARGS__); break; \
+                default: FN<2, kMomentumCombine>(__VA_ARGS__); break;            \
+            }                                                                    \
+        }                                                                        \
+    } while (0)
+
 void launch_chains(const Scratch &s, const Geometry &g, const float *A, const float *grads,
                    const uint32_t *sk, const uint32_t *si, uint32_t n, uint32_t max_slots,
                    uint32_t max_pieces, int cus, hipStream_t st)
 {
     if (n <= kLongRun) return;    // no row can have more than kLongRun updates
-    static int grid_p1[3] = {0, 0, 0}, grid_p3[3] = {0, 0, 0};
-    if (!grid_p1[g.nc]) {
-        grid_p1[g.nc] = g.nc == 1 ? resident_grid(long_piece_kernel<1, false>, cus) : resident_grid(long_piece_kernel<2, false>, cus);
-        grid_p3[g.nc] = g.nc == 1 ? resident_grid(long_piece_kernel<1, true>, cus) : resident_grid(long_piece_kernel<2, true>, cus);
-    }
-    const dim3 grid(cus * 8), block(256), gridp1(grid_p1[g.nc]), gridp3(grid_p3[g.nc]);
-    hipLaunchKernelGGL(long_find_kernel, grid, block, 0, st, sk, n, s.hdr, s.long_slot, s.long_head, max_slots);
-    hipLaunchKernelGGL(long_plan_kernel, grid, block, 0, st, sk, n, s.hdr, s.long_head, s.long_len, s.long_piece,
-                       s.long_count, s.long_base, s.piece_slot, max_slots, max_pieces);
-#define ECRM_CHAIN_LAUNCH(NC)                                                                               \
-    hipLaunchKernelGGL((long_piece_kernel<NC, false>), gridp1, block, 0, st, si, grads, s.hdr, s.long_head, \
-                       s.long_len, s.long_piece, s.long_base, s.piece_slot, s.partial, max_pieces, g);      \
-    hipLaunchKernelGGL((long_scan_kernel<NC>), grid, block, 0, st, sk, A, s.hdr, s.long_head, s.long_count, \
-                       s.long_base, s.partial, s.long_res, max_slots, g);                                   \
-    hipLaunchKernelGGL((long_piece_kernel<NC, true>), gridp3, block, 0, st, si, grads, s.hdr, s.long_head,  \
-                       s.long_len, s.long_piece, s.long_base, s.piece_slot, s.partial, max_pieces, g);      \
-    hipLaunchKernelGGL((long_reduce_kernel<NC>), grid, block, 0, st, s.hdr, s.long_count, s.long_base,      \
-                       s.partial, s.long_res, max_slots, g);
-    if (g.nc == 1) { ECRM_CHAIN_LAUNCH(1) } else { ECRM_CHAIN_LAUNCH(2) }
-#undef ECRM_CHAIN_LAUNCH
+    ECRM_DISPATCH(chains_for, s, g, A, grads, sk, si, n, max_slots, max_pieces, cus, st);
 }
 
 void launch_apply(const Scratch &s, const Geometry &g, float *E, float *A, float *PE, float *PA,
                   unsigned long long *load_data, unsigned long long *load_parity, const float *grads,
                   const uint32_t *sk, const uint32_t *si, uint32_t n, int cus, hipStream_t st)
 {
-    static int grid_apply[3] = {0, 0, 0};
-    if (!grid_apply[g.nc])
-        grid_apply[g.nc] = g.nc == 1 ? resident_grid(apply_stripes_kernel_d128, cus) : resident_grid(apply_stripes_kernel_d256, cus);
     ApplyArgs a;
     a.E = E; a.A = A; a.PE = PE; a.PA = PA;
     a.grads = grads; a.sk = sk; a.si = si;
@@ -736,10 +885,11 @@ void launch_apply(const Scratch &s, const Geometry &g, float *E, float *A, float
     a.hdr = s.hdr; a.cnt = s.cnt;
     a.load_data = load_data; a.load_parity = load_parity;
     a.n = n; a.geo = g;
-    const dim3 grid(grid_apply[g.nc]), block(256);
-    if (g.nc == 1) hipLaunchKernelGGL(apply_stripes_kernel_d128, grid, block, 0, st, a);
-    else hipLaunchKernelGGL(apply_stripes_kernel_d256, grid, block, 0, st, a);
+    if (g.mode == kAdagradCombine || g.mode == kMomentumCombine)      // one load count per modified entry
+        hipLaunchKernelGGL(count_rows_kernel, dim3(cus * 8), dim3(256), 0, st, sk, n, s.hdr, s.cnt, g.k, g.S);
+    ECRM_DISPATCH(apply_for, a, cus, st);
 }
+#undef ECRM_DISPATCH
 
 void launch_encode(const Geometry &g, const float *E, const float *A, float *PE, float *PA,
                    int grid_blocks, hipStream_t st)

@@ -19,8 +19,10 @@ def log(*a):
 
 
 class Case:
-    def __init__(self, R, D, k, S, max_batch, seed=0, lr=si.DEFAULT_LR, eps=si.DEFAULT_EPS):
+    def __init__(self, R, D, k, S, max_batch, seed=0, lr=si.DEFAULT_LR, eps=si.DEFAULT_EPS, optimizer=0,
+                 momentum=0.0, combine=0):
         self.R, self.D, self.k, self.S, self.seed, self.lr, self.eps = R, D, k, S, seed, lr, eps
+        self.optimizer, self.momentum, self.combine = optimizer, momentum, combine
         dev = "cuda:0"
         self.E = si.table(seed, si.TAG_E0, R, D, dev)
         self.A = si.table(seed, si.TAG_A0, R, D, dev)
@@ -28,7 +30,7 @@ class Case:
         self.PA = torch.zeros(R // k, D, device=dev)
         self.ld = torch.zeros(S, dtype=torch.int64, device=dev)
         self.lp = torch.zeros(S, dtype=torch.int64, device=dev)
-        self.ctx = Ecrm(R, D, k, S, lr, eps, max_batch)
+        self.ctx = Ecrm(R, D, k, S, lr, eps, max_batch, optimizer, momentum, combine)
         self.scratch = torch.empty(self.ctx.scratch_bytes(), dtype=torch.uint8, device=dev)
         self.ctx.bind(self.E, self.A, self.PE, self.PA, self.ld, self.lp, self.scratch)
         self.ctx.encode()
@@ -44,8 +46,13 @@ class Case:
         """keys_np: u64 host array; grads_t: [n, D] fp32 device tensor.  Runs both sides."""
         keys_t = torch.from_numpy(keys_np.view(np.int64)).to("cuda:0")
         self.ctx.update(keys_t, grads_t, n=len(keys_np))
-        oracle.update(self.hE, self.hA, self.hPE, self.hPA, self.k, self.S, self.lr, self.eps, keys_np,
-                      grads_t.cpu().numpy(), self.hld, self.hlp, threads=min(16, oracle.max_threads()))
+        if self.optimizer == 0 and self.combine == 0:
+            oracle.update(self.hE, self.hA, self.hPE, self.hPA, self.k, self.S, self.lr, self.eps, keys_np,
+                          grads_t.cpu().numpy(), self.hld, self.hlp, threads=min(16, oracle.max_threads()))
+        else:
+            oracle.update_rule(self.hE, self.hA, self.hPE, self.hPA, self.k, self.S, self.lr, self.eps,
+                               self.momentum, self.optimizer, self.combine, keys_np, grads_t.cpu().numpy(),
+                               self.hld, self.hlp)
 
     def compare(self, what=""):
         assert self.ctx.status() == 0

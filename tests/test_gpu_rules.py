@@ -1,0 +1,61 @@
+"""GPU parity of the other update rules (momentum SGD; combined / synchronous mode) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from ecrm_case import Case, grads_for, log
+
+pytestmark = pytest.mark.gpu
+
+RULES = [(1, 0), (0, 1), (1, 1)]          # (optimizer, combine); (0, 0) is covered by test_gpu_parity.py
+IDS = ["momentum", "adagrad-combined", "momentum-combined"]
+
+
+def _case(R, D, k, S, n, opt, comb, seed):
+    # velocities start from the A0 stream as well (small positive values): any state is legal
+    return Case(R, D, k, S, max_batch=n, seed=seed, optimizer=opt, momentum=0.9, combine=comb)
+
+
+@pytest.mark.parametrize("opt,comb", RULES, ids=IDS)
+@pytest.mark.parametrize("R,D,k,S,n", [(4 * 2000, 128, 4, 5, 30011), (10 * 300, 256, 10, 11, 9000),
+                                       (3 * 700, 36, 3, 4, 5000), (4 * 64, 200, 4, 8, 70000)])
+def test_rule_shapes(opt, comb, R, D, k, S, n):
+    c = _case(R, D, k, S, n, opt, comb, seed=61)
+    for call in range(2):
+        c.update(si.uniform_keys(61, call * n, n, R), grads_for(61, call * n, n, D))
+    log((opt, comb, R, D, k, S, n), c.compare("rules"))
+    c.check_invariant()
+
+
+@pytest.mark.parametrize("opt,comb", RULES, ids=IDS)
+@pytest.mark.parametrize("m", [1, 256, 257, 5000, 200000])
+def test_rule_one_hot_row(opt, comb, m):
+    R, D, k, S = 1 << 10, 128, 4, 5
+    c = _case(R, D, k, S, m, opt, comb, seed=67)
+    c.update(np.full(m, 321, np.uint64), grads_for(67, 0, m, D))
+    stats = c.ctx.batch_stats()
+    assert stats["long_rows"] == (1 if m > 256 else 0)
+    log("hot row", (opt, comb, m), stats, c.compare(f"hot{m}"))
+    c.check_invariant()
+    ld = c.ld.cpu().numpy()
+    assert int(ld.sum()) == (1 if comb else m)
+
+
+@pytest.mark.parametrize("opt,comb", RULES, ids=IDS)
+def test_rule_skewed_workload(opt, comb):
+    w = si.WORKLOADS["hbm_scale"]
+    shift = 8
+    R, per = w["R"] >> shift, (w["n"] >> shift) // w["batches"]
+    c = _case(R, si.DEFAULT_D, si.DEFAULT_K, si.DEFAULT_S, per, opt, comb, seed=w["seed"])
+    for b in range(2):
+        c.update(si.workload_keys("hbm_scale", batch=b, scale_shift=shift), grads_for(w["seed"], b * per, per, si.DEFAULT_D))
+    log("skewed", (opt, comb), c.ctx.batch_stats(), c.compare("skewed"))
+    c.check_invariant()
+
+
+def test_rule_config_errors():
+    from paper_2104_01981_amd import Ecrm, EcrmError
+    for kw in (dict(optimizer=2), dict(optimizer=1, momentum=1.0), dict(optimizer=1, momentum=-0.1), dict(combine=2)):
+        with pytest.raises(EcrmError):
+            Ecrm(4 * 100, 128, 4, 5, 0.01, 1e-8, 100, **kw)

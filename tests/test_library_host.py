@@ -29,7 +29,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def _create(lib, **kw):
-    base = dict(rows=1 << 14, dim=128, k=4, servers=5, optimizer=0, lr=0.01, eps=1e-8, max_batch=1 << 16)
+    base = dict(rows=1 << 14, dim=128, k=4, servers=5, optimizer=0, lr=0.01, eps=1e-8, max_batch=1 << 16,
+                momentum=0.0, combine=0)
     base.update(kw)
     cfg = binding.EcrmConfig(**base)
     ctx = C.c_void_p(0)
@@ -39,7 +40,8 @@ def _create(lib, **kw):
 
 @pytest.mark.parametrize("kw", [dict(rows=10), dict(rows=3), dict(dim=130), dict(dim=0), dict(dim=2048),
                                 dict(k=0), dict(k=65, rows=65 * 4, servers=70), dict(servers=4),
-                                dict(servers=2000), dict(optimizer=1), dict(lr=float("nan")), dict(eps=-1.0),
+                                dict(servers=2000), dict(optimizer=2), dict(optimizer=1, momentum=1.0), dict(combine=2),
+                                dict(lr=float("nan")), dict(eps=-1.0),
                                 dict(max_batch=0), dict(max_batch=(1 << 31) + 1), dict(rows=1 << 32)])
 def test_create_rejects_bad_config(lib, kw):
     rc, ctx = _create(lib, **kw)
