@@ -63,12 +63,17 @@ def main():
     ap.add_argument("--resident", type=int, default=0, help="batches kept resident and cycled through (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-recovery", action="store_true", help="skip the recovery-decode measurement")
-    ap.add_argument("--layout", default="arena", choices=["arena", "arena-rev", "arena-spread", "separate"])
-    ap.add_argument("--pads", default="", help="arena only: GiB of padding after E, A, PE (comma separated)")
+    ap.add_argument("--layout", default="arena", choices=["arena", "separate"],
+                    help="one arena in --order, or one torch allocation per array")
+    ap.add_argument("--placement-trials", type=int, default=2,
+                    help="how many arenas to try at most when the placement probe is slow")
+    ap.add_argument("--fresh-process-retry", type=int, default=1,
+                    help="if every arena of this process probes slow, release the memory and run the benchmark "
+                         "once more in a child process (0 disables)")
+    ap.add_argument("--placement-accept-frac", type=float, default=0.67,
+                    help="the probe accepts an arena when the apply kernel reaches this fraction of the HBM peak")
     ap.add_argument("--order", default="E,g0,g1,A,g2,g3,PE,PA,scratch,keys,g*",
                     help="arena only: order of the resident arrays (gN = batch N, padN = N GiB of padding)")
-    ap.add_argument("--skew", type=int, default=0,
-                    help="extra bytes (multiple of 256) by which each successive resident array is shifted")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain device-to-device copies of 8 GiB (to scale rocprof's HBM byte counters)")
     ap.add_argument("--per-step", action="store_true",
@@ -119,94 +124,135 @@ def main():
     t_setup = time.perf_counter()
     ctx = Ecrm(R, D, k, S, si.DEFAULT_LR, si.DEFAULT_EPS, per, optimizer=1 if args.optimizer == "momentum" else 0,
                momentum=0.9 if args.optimizer == "momentum" else 0.0, combine=1 if args.combine else 0)
-    # one arena for everything that stays resident (tables, scratch, all batches), carved at 2 MiB
+    # One arena for everything that stays resident (tables, scratch, all batches), carved at 2 MiB.
+    # Order matters on this device: tables that are swept together must start >= 32 GiB apart (see
+    # the design doc), so batches are placed between them.
     ALIGN = 2 << 20
     sizes = {"E": R * D * 4, "A": R * D * 4, "PE": R // k * D * 4, "PA": R // k * D * 4, "ld": S * 8, "lp": S * 8,
              "scratch": ctx.scratch_bytes()}
     for b in range(nb):
         sizes[f"keys{b}"] = per * 8
         sizes[f"grads{b}"] = per * D * 4
-    if args.layout == "arena-rev":
-        sizes = dict(reversed(list(sizes.items())))
-    if args.layout == "arena-spread":          # the four tables far apart, batches in between
-        order, gi = [], 0
-        per_gap = max(1, nb // 4)
-        for t in ("E", "A", "PE", "PA"):
-            order.append(t)
-            for _ in range(per_gap):
-                if gi < nb:
-                    order.append(f"grads{gi}")
-                    gi += 1
-        order += [f"grads{b}" for b in range(gi, nb)] + [f"keys{b}" for b in range(nb)] + ["scratch", "ld", "lp"]
-        sizes = {name: sizes[name] for name in order}
-    if args.order:
-        order, npad = [], 0
-        for tok in args.order.split(","):
-            if tok == "g*":
-                order += [f"grads{b}" for b in range(nb) if f"grads{b}" not in order]
-            elif tok == "keys":
-                order += [f"keys{b}" for b in range(nb)]
-            elif tok.startswith("pad"):
-                sizes[f"_pad{npad}"] = int(float(tok[3:]) * (1 << 30))
-                order.append(f"_pad{npad}")
-                npad += 1
-            elif tok.startswith("g"):
-                if int(tok[1:]) < nb:
-                    order.append(f"grads{int(tok[1:])}")
-            else:
-                order.append(tok)
-        order += [n_ for n_ in sizes if n_ not in order]
-        sizes = {name: sizes[name] for name in order}
-    pads = dict(zip(("E", "A", "PE"), [int(float(x) * (1 << 30)) for x in args.pads.split(",")])) if args.pads else {}
+    order, npad = [], 0
+    for tok in args.order.split(","):
+        if tok == "g*":
+            order += [f"grads{b}" for b in range(nb) if f"grads{b}" not in order]
+        elif tok == "keys":
+            order += [f"keys{b}" for b in range(nb)]
+        elif tok.startswith("pad"):
+            sizes[f"_pad{npad}"] = int(float(tok[3:]) * (1 << 30))
+            order.append(f"_pad{npad}")
+            npad += 1
+        elif tok.startswith("g"):
+            if int(tok[1:]) < nb:
+                order.append(f"grads{int(tok[1:])}")
+        elif tok:
+            order.append(tok)
+    order += [n_ for n_ in sizes if n_ not in order]
     offs, total = {}, 0
-    for i, (name, sz) in enumerate(sizes.items()):
-        offs[name] = total + i * args.skew
-        total += (sz + ALIGN - 1) // ALIGN * ALIGN + pads.get(name, 0)
-    total += len(sizes) * args.skew
-    if args.layout == "separate":
-        pieces = {name: torch.empty(sz, dtype=torch.uint8, device=dev) for name, sz in sizes.items()}
-
-        def carve(name, dtype, shape):
-            return pieces[name].view(dtype).view(shape)
-    else:
-        arena = torch.empty(total, dtype=torch.uint8, device=dev)
-
-        def carve(name, dtype, shape):
-            return arena[offs[name]:offs[name] + sizes[name]].view(dtype).view(shape)
-
-    E, A = carve("E", torch.float32, (R, D)), carve("A", torch.float32, (R, D))
-    PE, PA = carve("PE", torch.float32, (R // k, D)), carve("PA", torch.float32, (R // k, D))
-    ld, lp = carve("ld", torch.int64, (S,)), carve("lp", torch.int64, (S,))
-    scratch = carve("scratch", torch.uint8, (sizes["scratch"],))
+    for name in order:
+        offs[name] = total
+        total += (sizes[name] + ALIGN - 1) // ALIGN * ALIGN
     CH = 1 << 22                                  # rows generated per slice (2 GiB of fp32 at D = 128)
-    for r0 in range(0, R, CH):
-        r1 = min(R, r0 + CH)
-        E[r0:r1] = si.values(seed, si.TAG_E0, r0 * D, (r1 - r0) * D, dev).view(r1 - r0, D)
-        A[r0:r1] = si.values(seed, si.TAG_A0, r0 * D, (r1 - r0) * D, dev).view(r1 - r0, D)
-    ld.zero_()
-    lp.zero_()
-    ctx.bind(E, A, PE, PA, ld, lp, scratch)
-    ctx.encode()
 
-    keys, grads, alg_path, alg_apply = [], [], [], []
-    for b in range(nb):
-        kt = carve(f"keys{b}", torch.int64, (per,))
+    def fill_tables():
+        for r0 in range(0, R, CH):
+            r1 = min(R, r0 + CH)
+            E[r0:r1] = si.values(seed, si.TAG_E0, r0 * D, (r1 - r0) * D, dev).view(r1 - r0, D)
+            A[r0:r1] = si.values(seed, si.TAG_A0, r0 * D, (r1 - r0) * D, dev).view(r1 - r0, D)
+        ld.zero_()
+        lp.zero_()
+        ctx.encode()
+
+    def fill_batch(b):
         kg = si.workload_keys_t(args.workload, b, sh, dev)
-        kt.copy_(torch.where(kg >= R, kg - R, kg))          # only differs when k does not divide 2^m
-        keys.append(kt)
-        gt = carve(f"grads{b}", torch.float32, (per, D))
+        keys[b].copy_(torch.where(kg >= R, kg - R, kg))      # only differs when k does not divide 2^m
         for i0 in range(0, per, CH):
             i1 = min(per, i0 + CH)
-            gt[i0:i1] = si.grads(seed, b * per + i0, i1 - i0, D, dev)
-        grads.append(gt)
-        # measurement only: rows / stripes this batch touches, items on rows with long runs
+            grads[b][i0:i1] = si.grads(seed, b * per + i0, i1 - i0, D, dev)
+
+    def batch_bytes(kt):
+        """(whole-path, apply-kernel) algorithmic bytes of one batch -- measurement only, from the keys."""
         uk, cnt = torch.unique(kt, return_counts=True)
         U = int(uk.numel())
         Up = int(torch.unique(uk // k).numel())
         n_long = int(cnt[cnt > 256].sum())
-        alg_path.append(per * (8 + 4 * D) + (U + Up) * 16 * D)
-        alg_apply.append(per * 8 + (per - n_long) * 4 * D + (U + Up) * 16 * D)
-        del uk, cnt
+        return per * (8 + 4 * D) + (U + Up) * 16 * D, per * 8 + (per - n_long) * 4 * D + (U + Up) * 16 * D
+
+    # Physical placement is the driver's; now and then (e.g. right after another process released a
+    # lot of memory) the same virtual layout lands badly and every kernel that sweeps the tables runs
+    # ~15 % slower for the life of the allocation.  Probe with three updates of batch 0 and, if the
+    # apply kernel is clearly off its usual rate, release the arena and take a new one.
+    placement = []
+    for trial in range(max(1, args.placement_trials)):
+        if args.layout == "separate":
+            pieces = {name: torch.empty(sizes[name], dtype=torch.uint8, device=dev) for name in order}
+
+            def carve(name, dtype, shape):
+                return pieces[name].view(dtype).view(shape)
+        else:
+            arena = torch.empty(total, dtype=torch.uint8, device=dev)
+
+            def carve(name, dtype, shape):
+                return arena[offs[name]:offs[name] + sizes[name]].view(dtype).view(shape)
+
+        E, A = carve("E", torch.float32, (R, D)), carve("A", torch.float32, (R, D))
+        PE, PA = carve("PE", torch.float32, (R // k, D)), carve("PA", torch.float32, (R // k, D))
+        ld, lp = carve("ld", torch.int64, (S,)), carve("lp", torch.int64, (S,))
+        scratch = carve("scratch", torch.uint8, (sizes["scratch"],))
+        keys = [carve(f"keys{b}", torch.int64, (per,)) for b in range(nb)]
+        grads = [carve(f"grads{b}", torch.float32, (per, D)) for b in range(nb)]
+        ctx.bind(E, A, PE, PA, ld, lp, scratch)
+        fill_tables()
+        fill_batch(0)
+        ctx.update(keys[0], grads[0])
+        ctx.profile(True)
+        ctx.profile_read()
+        for _ in range(3):
+            ctx.update(keys[0], grads[0])
+        pms, pcalls = ctx.profile_read()
+        ctx.profile(False)
+        assert ctx.status() == 0
+        probe_frac = batch_bytes(keys[0])[1] / (pms[2] / pcalls * 1e-3) / 1e9 / HBM_PEAK_GBS
+        placement.append(round(probe_frac, 4))
+        if trial + 1 >= args.placement_trials or probe_frac >= args.placement_accept_frac:
+            break
+        log(f"placement trial {trial}: apply kernel at {probe_frac:.3f} of the HBM peak, taking another arena")
+        blocker = torch.empty(8 << 30, dtype=torch.uint8, device=dev)     # keeps the next arena off the same pages
+        ctx.drop_buffers()
+        del E, A, PE, PA, ld, lp, scratch, keys, grads
+        if args.layout == "separate":
+            del pieces
+        else:
+            del arena
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        del blocker
+    if placement[-1] < args.placement_accept_frac and args.fresh_process_retry > 0:
+        # every arena this process obtained is slow: hand over to a child process with fresh mappings
+        import subprocess
+        log(f"placement: {len(placement)} arenas at {placement} of the HBM peak; retrying in a fresh process")
+        ctx.drop_buffers()
+        del E, A, PE, PA, ld, lp, scratch, keys, grads
+        if args.layout == "separate":
+            del pieces
+        else:
+            del arena
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        argv = [a for a in sys.argv[1:]]
+        rc = subprocess.call([sys.executable, os.path.abspath(__file__), *argv, "--fresh-process-retry", "0"],
+                             env=dict(os.environ, ECRM_BENCH_PARENT_PROBES=json.dumps(placement)))
+        sys.exit(rc)
+    fill_tables()                                  # the probe's updates are undone: tables start from the recipe
+
+    alg_path, alg_apply = [], []
+    for b in range(nb):
+        if b:
+            fill_batch(b)
+        bp, ba = batch_bytes(keys[b])
+        alg_path.append(bp)
+        alg_apply.append(ba)
     torch.cuda.synchronize()
     log(f"setup {time.perf_counter() - t_setup:.1f}s: R={R} D={D} k={k} S={S} batches={nb}x{per}, "
         f"scratch {ctx.scratch_bytes() / 2**20:.0f} MiB, "
@@ -264,6 +310,8 @@ def main():
                      "traffic": measured_traffic(args.workload, sh, variant),
                      "algorithmic_bytes_per_launch": apply_bytes, "avg_launch_ms": apply_ms},
         "phases_ms_per_step": {"group": ms[0] / calls, "chains": ms[1] / calls, "apply": apply_ms},
+        "placement": {"arenas_tried": len(placement), "probe_apply_frac": placement,
+                      "parent_process_probes": json.loads(os.environ.get("ECRM_BENCH_PARENT_PROBES", "null"))},
         "path": {"algorithmic_bytes_per_step": path_bytes, "achieved_GBps": path_gbs,
                  "frac_of_hbm_peak": path_gbs / HBM_PEAK_GBS},
     }

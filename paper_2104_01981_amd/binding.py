@@ -137,6 +137,10 @@ class Ecrm:
             raise EcrmError(rc, "ecrm_bind")
         self._keep = (E, A, PE, PA, load_data, load_parity, scratch)
 
+    def drop_buffers(self):
+        """Python side only: stop keeping the bound tensors alive (bind again before any further call)."""
+        self._keep = None
+
     def encode(self, stream=None):
         rc = self._lib.ecrm_encode(self._ctx, _stream(stream))
         if rc != ECRM_OK:

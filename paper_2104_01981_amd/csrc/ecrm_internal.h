@@ -13,8 +13,11 @@ constexpr int kWave = 64;            // CDNA wavefront
 
 constexpr int kSortThreads = 512;    // 8 waves per sort block
 constexpr int kSortWaves = kSortThreads / kWave;
-constexpr int kSortIpt = 16;         // items per thread
-constexpr int kSortTile = kSortThreads * kSortIpt;   // 8192 items per block
+#ifndef ECRM_SORT_IPT
+#define ECRM_SORT_IPT 12
+#endif
+constexpr int kSortIpt = ECRM_SORT_IPT;   // items per thread
+constexpr int kSortTile = kSortThreads * kSortIpt;   // 6144 items per block: 68 KB of LDS, two blocks per CU
 constexpr int kMaxRadixBits = 9;
 constexpr int kMaxBins = 1 << kMaxRadixBits;
 constexpr uint32_t kLongRun = ECRM_LONG_RUN;  // rows with more updates than this use the split-chain path

@@ -192,7 +192,7 @@ __global__ __launch_bounds__(256) void long_find_kernel(const uint32_t *sk, uint
     }
 }
 
-// Length of each long run (binary search for its end) and its cut into pieces.
+// Length of each long run (binary search for its end) and its cut into pieces.  One wave per run.
 __global__ __launch_bounds__(256) void long_plan_kernel(const uint32_t *sk, uint32_t n, Header *hdr,
                                                         const uint32_t *long_head, uint32_t *long_len,
                                                         uint32_t *long_piece, uint32_t *long_count,
@@ -201,26 +201,30 @@ __global__ __launch_bounds__(256) void long_plan_kernel(const uint32_t *sk, uint
 {
     if (hdr->batch_bad) return;
     const uint32_t nl = min(hdr->n_long, max_slots);
-    const uint32_t stride = gridDim.x * blockDim.x;
-    for (uint32_t slot = blockIdx.x * blockDim.x + threadIdx.x; slot < nl; slot += stride) {
-        const uint32_t p = long_head[slot];
-        const uint32_t x = sk[p];
+    const uint32_t lane = lane_id();
+    for (uint32_t slot = wave_id(); slot < nl; slot += wave_count()) {
+        const uint32_t p = uniform(long_head[slot]);
+        const uint32_t x = uniform(sk[p]);
         uint32_t lo = p + kLongRun, hi = n;            // sk[lo] == x, sk[hi] != x (hi == n: past the end)
         while (hi - lo > 1) {
             const uint32_t mid = lo + (hi - lo) / 2;
-            if (sk[mid] == x) lo = mid; else hi = mid;
+            if (uniform(sk[mid]) == x) lo = mid; else hi = mid;
         }
         const uint32_t L = hi - p;
         uint32_t C = (L + kPieceMaxCount - 1) / kPieceMaxCount;
         if (C < kPieceMin) C = kPieceMin;
         const uint32_t P = (L + C - 1) / C;
-        const uint32_t base = atomicAdd(&hdr->n_pieces, P);
-        atomicAdd(&hdr->n_long_items, (unsigned long long)L);
-        long_len[slot] = L;
-        long_piece[slot] = C;
-        long_count[slot] = P;
-        long_base[slot] = base;
-        for (uint32_t j = 0; j < P; ++j)
+        uint32_t base = 0;
+        if (lane == 0) {
+            base = atomicAdd(&hdr->n_pieces, P);
+            atomicAdd(&hdr->n_long_items, (unsigned long long)L);
+            long_len[slot] = L;
+            long_piece[slot] = C;
+            long_count[slot] = P;
+            long_base[slot] = base;
+        }
+        base = uniform(base);
+        for (uint32_t j = lane; j < P; j += kWave)
             if (base + j < max_pieces) piece_slot[base + j] = slot;   // always true by the bound on pieces
     }
 }
@@ -292,54 +296,117 @@ __global__ __launch_bounds__(256) void long_piece_kernel(const uint32_t *si, con
     }
 }
 
+constexpr int kRowWaves = 16;      // waves that share one long row in the scan and reduce kernels
+
 // Phase 2: exclusive scan of the pieces' summaries, seeded with the stored state, so that every
 // piece knows the state it starts from: Adagrad adds the sums of squares; momentum composes
 // v -> mu^len * v + V_piece.  long_res[slot][1] receives the state after the whole run.
-// One wave per long row.
+// One block of 16 waves per long row: every wave folds a contiguous range of pieces, the ranges'
+// results are exchanged through LDS, and every wave then rewrites its range with the prefixes.
 template <int NC, int MODE>
-__global__ __launch_bounds__(256) void long_scan_kernel(const uint32_t *sk, const float *A, Header *hdr,
-                                                        const uint32_t *long_head, const uint32_t *long_count,
-                                                        const uint32_t *long_base, const uint32_t *long_len,
-                                                        const uint32_t *long_piece, double *partial,
-                                                        double *long_res, uint32_t max_slots, Geometry geo)
+__global__ __launch_bounds__(kRowWaves * kWave) void long_scan_kernel(
+    const uint32_t *sk, const float *A, Header *hdr, const uint32_t *long_head, const uint32_t *long_count,
+    const uint32_t *long_base, const uint32_t *long_len, const uint32_t *long_piece, double *partial,
+    double *long_res, uint32_t max_slots, Geometry geo)
 {
+    __shared__ double s_fold[kRowWaves][NC][2][kWave];
     if (hdr->batch_bad) return;
     const uint32_t nl = min(hdr->n_long, max_slots);
-    const uint32_t D = geo.D;
+    const uint32_t D = geo.D, lane = lane_id(), w = threadIdx.x / kWave;
     constexpr uint32_t U = 8;
-    for (uint32_t slot = wave_id(); slot < nl; slot += wave_count()) {
+    for (uint32_t slot = blockIdx.x; slot < nl; slot += gridDim.x) {
         const uint32_t x = uniform(sk[long_head[slot]]);
         const uint32_t P = uniform(long_count[slot]), base = uniform(long_base[slot]);
-        // momentum: decay over a full piece and over the (shorter) last one
-        double decay_full = 1.0, decay_last = 1.0;
-        if (MODE == kMomentumSeq) {
-            const uint32_t C = uniform(long_piece[slot]), L = uniform(long_len[slot]);
-            decay_full = pow((double)geo.mu, (double)C);
-            decay_last = pow((double)geo.mu, (double)(L - (P - 1) * C));
-        }
+        const uint32_t C = uniform(long_piece[slot]), L = uniform(long_len[slot]);
+        const uint32_t Q = (P + kRowWaves - 1) / kRowWaves;          // pieces per wave
+        const uint32_t j_lo = min(w * Q, P), j_hi = min(j_lo + Q, P);
+        // momentum: decay over one full piece, over the run's (shorter) last piece
+        const double mu = (double)geo.mu;
+        const double decay_full = MODE == kMomentumSeq ? pow(mu, (double)C) : 1.0;
+        const double decay_last = MODE == kMomentumSeq ? pow(mu, (double)(L - (P - 1) * C)) : 1.0;
         for (uint32_t cb = 0; cb < geo.ncb; ++cb) {
             const uint32_t col0 = cb * NC * 128u;
-            const rsrc_t arow = row_f32(A, x, D, col0);
-            D2 G[NC];
+            // (a) fold of this wave's range, started from zero
+            D2 f[NC];
 #pragma unroll
-            for (int i = 0; i < NC; ++i) G[i] = widen2(ld2(arow, i));
-            for (uint32_t j0 = 0; j0 < P; j0 += U) {
+            for (int i = 0; i < NC; ++i) f[i] = D2{0, 0};
+            for (uint32_t j0 = j_lo; j0 < j_hi; j0 += U) {
                 D2 t[U][NC];
 #pragma unroll
                 for (uint32_t u = 0; u < U; ++u) {
-                    const rsrc_t r = row_f64(partial, base + min(j0 + u, P - 1), D, col0);
+                    const rsrc_t r = row_f64(partial, base + min(j0 + u, j_hi - 1), D, col0);
 #pragma unroll
                     for (int i = 0; i < NC; ++i) t[u][i] = ldd2(r, i);
                 }
 #pragma unroll
                 for (uint32_t u = 0; u < U; ++u) {
-                    if (j0 + u < P) {
+                    if (j0 + u < j_hi) {
+                        const double dec = j0 + u + 1 == P ? decay_last : decay_full;
+#pragma unroll
+                        for (int i = 0; i < NC; ++i) {
+                            if (MODE == kMomentumSeq) {
+                                f[i].x = fma(dec, f[i].x, t[u][i].x);
+                                f[i].y = fma(dec, f[i].y, t[u][i].y);
+                            } else {
+                                f[i].x += t[u][i].x;
+                                f[i].y += t[u][i].y;
+                            }
+                        }
+                    }
+                }
+            }
+            __syncthreads();                                         // previous column block's reads are done
+#pragma unroll
+            for (int i = 0; i < NC; ++i) {
+                s_fold[w][i][0][lane] = f[i].x;
+                s_fold[w][i][1][lane] = f[i].y;
+            }
+            __syncthreads();
+            // (b) state at the start of this wave's range (and, for wave 0, after the whole run)
+            const rsrc_t arow = row_f32(A, x, D, col0);
+            D2 G[NC], total[NC];
+#pragma unroll
+            for (int i = 0; i < NC; ++i) {
+                G[i] = widen2(ld2(arow, i));
+                total[i] = G[i];
+            }
+            for (uint32_t u = 0; u < (uint32_t)kRowWaves; ++u) {
+                const uint32_t u_lo = min(u * Q, P), u_hi = min(u_lo + Q, P);
+                if (u_lo == u_hi) break;
+                double dec = 1.0;
+                if (MODE == kMomentumSeq) {
+                    const uint32_t items = u_hi == P ? L - u_lo * C : (u_hi - u_lo) * C;
+                    dec = pow(mu, (double)items);
+                }
+#pragma unroll
+                for (int i = 0; i < NC; ++i) {
+                    const double fx = s_fold[u][i][0][lane], fy = s_fold[u][i][1][lane];
+                    if (u < w) {
+                        G[i].x = MODE == kMomentumSeq ? fma(dec, G[i].x, fx) : G[i].x + fx;
+                        G[i].y = MODE == kMomentumSeq ? fma(dec, G[i].y, fy) : G[i].y + fy;
+                    }
+                    total[i].x = MODE == kMomentumSeq ? fma(dec, total[i].x, fx) : total[i].x + fx;
+                    total[i].y = MODE == kMomentumSeq ? fma(dec, total[i].y, fy) : total[i].y + fy;
+                }
+            }
+            // (c) rewrite this wave's range with the prefixes
+            for (uint32_t j0 = j_lo; j0 < j_hi; j0 += U) {
+                D2 t[U][NC];
+#pragma unroll
+                for (uint32_t u = 0; u < U; ++u) {
+                    const rsrc_t r = row_f64(partial, base + min(j0 + u, j_hi - 1), D, col0);
+#pragma unroll
+                    for (int i = 0; i < NC; ++i) t[u][i] = ldd2(r, i);
+                }
+#pragma unroll
+                for (uint32_t u = 0; u < U; ++u) {
+                    if (j0 + u < j_hi) {
                         const rsrc_t r = row_f64(partial, base + j0 + u, D, col0);
+                        const double dec = j0 + u + 1 == P ? decay_last : decay_full;
 #pragma unroll
                         for (int i = 0; i < NC; ++i) {
                             std2(r, i, G[i]);
                             if (MODE == kMomentumSeq) {
-                                const double dec = j0 + u + 1 == P ? decay_last : decay_full;
                                 G[i].x = fma(dec, G[i].x, t[u][i].x);
                                 G[i].y = fma(dec, G[i].y, t[u][i].y);
                             } else {
@@ -350,41 +417,47 @@ __global__ __launch_bounds__(256) void long_scan_kernel(const uint32_t *sk, cons
                     }
                 }
             }
-            const rsrc_t res = row_f64(long_res, (size_t)slot * 2 + 1, D, col0);
+            if (w == 0) {
+                const rsrc_t res = row_f64(long_res, (size_t)slot * 2 + 1, D, col0);
 #pragma unroll
-            for (int i = 0; i < NC; ++i) std2(res, i, G[i]);
+                for (int i = 0; i < NC; ++i) std2(res, i, total[i]);
+            }
         }
     }
 }
 
-// Phase 4: long_res[slot][0] = sum over the pieces, in order, of their step sums.
+// Phase 4: long_res[slot][0] = sum over the pieces of their step sums (16 waves per long row: ranges
+// of pieces are summed in order, then the ranges' sums in order).
 template <int NC>
-__global__ __launch_bounds__(256) void long_reduce_kernel(Header *hdr, const uint32_t *long_count,
-                                                          const uint32_t *long_base, const double *partial,
-                                                          double *long_res, uint32_t max_slots, Geometry geo)
+__global__ __launch_bounds__(kRowWaves * kWave) void long_reduce_kernel(Header *hdr, const uint32_t *long_count,
+                                                                        const uint32_t *long_base, const double *partial,
+                                                                        double *long_res, uint32_t max_slots, Geometry geo)
 {
+    __shared__ double s_fold[kRowWaves][NC][2][kWave];
     if (hdr->batch_bad) return;
     const uint32_t nl = min(hdr->n_long, max_slots);
-    const uint32_t D = geo.D;
+    const uint32_t D = geo.D, lane = lane_id(), w = threadIdx.x / kWave;
     constexpr uint32_t U = 8;
-    for (uint32_t slot = wave_id(); slot < nl; slot += wave_count()) {
+    for (uint32_t slot = blockIdx.x; slot < nl; slot += gridDim.x) {
         const uint32_t P = uniform(long_count[slot]), base = uniform(long_base[slot]);
+        const uint32_t Q = (P + kRowWaves - 1) / kRowWaves;
+        const uint32_t j_lo = min(w * Q, P), j_hi = min(j_lo + Q, P);
         for (uint32_t cb = 0; cb < geo.ncb; ++cb) {
             const uint32_t col0 = cb * NC * 128u;
             D2 s[NC];
 #pragma unroll
             for (int i = 0; i < NC; ++i) s[i] = D2{0, 0};
-            for (uint32_t j0 = 0; j0 < P; j0 += U) {
+            for (uint32_t j0 = j_lo; j0 < j_hi; j0 += U) {
                 D2 t[U][NC];
 #pragma unroll
                 for (uint32_t u = 0; u < U; ++u) {
-                    const rsrc_t r = row_f64(partial, base + min(j0 + u, P - 1), D, col0);
+                    const rsrc_t r = row_f64(partial, base + min(j0 + u, j_hi - 1), D, col0);
 #pragma unroll
                     for (int i = 0; i < NC; ++i) t[u][i] = ldd2(r, i);
                 }
 #pragma unroll
                 for (uint32_t u = 0; u < U; ++u) {
-                    if (j0 + u < P) {
+                    if (j0 + u < j_hi) {
 #pragma unroll
                         for (int i = 0; i < NC; ++i) {
                             s[i].x += t[u][i].x;
@@ -393,9 +466,25 @@ __global__ __launch_bounds__(256) void long_reduce_kernel(Header *hdr, const uin
                     }
                 }
             }
-            const rsrc_t res = row_f64(long_res, (size_t)slot * 2 + 0, D, col0);
+            __syncthreads();
 #pragma unroll
-            for (int i = 0; i < NC; ++i) std2(res, i, s[i]);
+            for (int i = 0; i < NC; ++i) {
+                s_fold[w][i][0][lane] = s[i].x;
+                s_fold[w][i][1][lane] = s[i].y;
+            }
+            __syncthreads();
+            if (w == 0) {
+                const rsrc_t res = row_f64(long_res, (size_t)slot * 2 + 0, D, col0);
+#pragma unroll
+                for (int i = 0; i < NC; ++i) {
+                    D2 tot = D2{0, 0};
+                    for (int u = 0; u < kRowWaves; ++u) {
+                        tot.x += s_fold[u][i][0][lane];
+                        tot.y += s_fold[u][i][1][lane];
+                    }
+                    std2(res, i, tot);
+                }
+            }
         }
     }
 }
@@ -825,12 +914,12 @@ static void chains_for(const Scratch &s, const Geometry &g, const float *A, cons
     hipLaunchKernelGGL((long_piece_kernel<NC, false, MODE>), dim3(grid_p1), block, 0, st, si, grads, s.hdr, s.long_head,
                        s.long_len, s.long_piece, s.long_base, s.piece_slot, s.partial, max_pieces, g);
     if (!Rule<MODE>::combine) {
-        hipLaunchKernelGGL((long_scan_kernel<NC, MODE>), grid, block, 0, st, sk, A, s.hdr, s.long_head, s.long_count,
+        hipLaunchKernelGGL((long_scan_kernel<NC, MODE>), dim3(cus * 2), dim3(kRowWaves * kWave), 0, st, sk, A, s.hdr, s.long_head, s.long_count,
                            s.long_base, s.long_len, s.long_piece, s.partial, s.long_res, max_slots, g);
         hipLaunchKernelGGL((long_piece_kernel<NC, true, MODE>), dim3(grid_p3), block, 0, st, si, grads, s.hdr,
                            s.long_head, s.long_len, s.long_piece, s.long_base, s.piece_slot, s.partial, max_pieces, g);
     }
-    hipLaunchKernelGGL((long_reduce_kernel<NC>), grid, block, 0, st, s.hdr, s.long_count, s.long_base, s.partial,
+    hipLaunchKernelGGL((long_reduce_kernel<NC>), dim3(cus * 2), dim3(kRowWaves * kWave), 0, st, s.hdr, s.long_count, s.long_base, s.partial,
                        s.long_res, max_slots, g);
 }
 
