@@ -16,7 +16,9 @@
 //
 // One wavefront works on one row at a time: 64 lanes x float2 = a 128-float slice, so a load
 // instruction of the wave moves 512 contiguous bytes from a wave-uniform (scalar) row address, and
-// all control flow is wave-uniform.  All chain arithmetic is carried in fp64.
+// all control flow is wave-uniform.  All chain arithmetic is carried in fp64.  The kernels are
+// templated on the update rule (struct Rule below): Adagrad or momentum SGD, updates of an entry
+// applied one by one or combined; the description above is the Adagrad, one-by-one case.
 #include "ecrm_internal.h"
 
 namespace ecrm {
@@ -891,9 +893,6 @@ static int resident_grid(K kernel, int cus)
 {
     int per_cu = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess || per_cu < 1) per_cu = 4;
-#ifdef ECRM_BLOCKS_PER_CU
-    if (per_cu > ECRM_BLOCKS_PER_CU) per_cu = ECRM_BLOCKS_PER_CU;
-#endif
     return cus * per_cu;
 }
 

@@ -206,3 +206,33 @@ def test_profile_hooks():
     c.ctx.profile(False)
     c.ctx.update(kt, g)
     assert c.ctx.profile_read()[1] == 0
+
+
+def test_update_inside_a_hip_graph():
+    """ecrm_update only enqueues kernels (no memsets, no synchronisation), so a caller may capture it.
+    Replays are checked one by one against eager calls on a twin, with eager work in between."""
+    R, D, k, S, n = 4 * 2000, 128, 4, 5, 20000
+    a = Case(R, D, k, S, max_batch=n, seed=71)
+    b = Case(R, D, k, S, max_batch=n, seed=71)
+    keys = si.uniform_keys(71, 0, n, R)
+    keys[::7] = 4321                                   # a long run as well
+    kt = torch.from_numpy(keys.view(np.int64)).cuda()
+    g = grads_for(71, 0, n, D)
+    a.ctx.update(kt, g)                                # warm-up outside the capture (first-call set-up)
+    b.ctx.update(kt, g)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        a.ctx.update(kt, g, stream=side)
+    b.ctx.update(kt, g)                                # the capture itself ran nothing on a; this call belongs to
+    graph.replay()                                     # ... the first replay
+    for rep in range(4):
+        torch.cuda.synchronize()
+        for x, y in zip((a.E, a.A, a.PE, a.PA, a.ld, a.lp), (b.E, b.A, b.PE, b.PA, b.ld, b.lp)):
+            assert torch.equal(x, y), f"replay {rep}"
+        (a.E.sum() + b.E.sum()).item()                 # unrelated eager work and a sync between replays
+        graph.replay()
+        b.ctx.update(kt, g)
+    torch.cuda.synchronize()
+    assert torch.equal(a.E, b.E) and torch.equal(a.PA, b.PA)
+    assert a.ctx.status() == 0
