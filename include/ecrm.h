@@ -40,7 +40,9 @@ enum {
     ECRM_ESCRATCH = -3,  /* scratch buffer missing, misaligned or too small                */
     ECRM_EBATCH = -4,    /* n exceeds config.max_batch                                     */
     ECRM_EKEYRANGE = -5, /* a key >= rows was seen on the device (reported by ecrm_status) */
-    ECRM_EHIP = -6       /* a HIP runtime call failed                                      */
+    ECRM_EHIP = -6,      /* a HIP runtime call failed                                      */
+    ECRM_EBUFFER = -7,   /* recovery buffer full on the device (reported by ecrm_status)   */
+    ECRM_ESTATE = -8     /* call not allowed in the current recovery state                 */
 };
 
 enum { ECRM_OPT_ADAGRAD = 0, ECRM_OPT_MOMENTUM = 1 };
@@ -129,8 +131,41 @@ int ecrm_recover_server(ecrm_ctx *ctx, uint32_t server, void *hip_stream);
 int ecrm_degraded_read(ecrm_ctx *ctx, const uint64_t *keys, uint64_t n, uint32_t lost_server,
                        float *out_E, float *out_A, void *hip_stream);
 
+/* Training while a failed server is being rebuilt (Sec. 3.4 "Training during recovery").  The
+ * stripes are split into `chunks` equal ranges that are rebuilt one after the other; while a chunk
+ * is "locked", every update that touches one of its stripes is buffered instead of applied, and it
+ * is applied when the chunk is released -- so the decoder never sees an entry and a parity at
+ * different versions, and training never pauses.  Independently of the lock, an update to an entry
+ * that the failed server held is buffered until that entry has been rebuilt.  More chunks mean a
+ * smaller buffer and more switches (the paper's 1 lock vs 10 locks).  Buffered updates keep their
+ * arrival order per entry; their load is counted when they are applied.
+ *
+ *   ecrm_recovery_begin   declares `server` lost (its rows are NOT overwritten; use ecrm_fail_server
+ *                         in tests) and hands over the buffer: device memory for 2*capacity keys
+ *                         (u64) and 2*capacity gradient rows, capacity <= max_batch.
+ *   ecrm_recovery_lock    host-side only: from now on ecrm_update buffers what touches the next chunk.
+ *   ecrm_recovery_decode  enqueues the reconstruction of the locked chunk.  It may run on another
+ *                         stream than the updates, provided it starts after every ecrm_update that was
+ *                         enqueued BEFORE the lock has finished (an event from that stream).
+ *   ecrm_recovery_unlock  call on the update stream once the decode has finished (wait for its event
+ *                         first).  SYNCHRONISES the stream to learn how many updates are waiting,
+ *                         releases the chunk and enqueues the replay of the buffer (what must keep
+ *                         waiting goes back into the buffer).  After the last chunk the recovery ends.
+ *   ecrm_recovery_state   waits for the stream; reports whether a recovery is active, the number of
+ *                         chunks rebuilt, the number of chunks, and how many updates are waiting.
+ * A batch whose held-back items do not fit the buffer is rejected as a whole (sticky EBUFFER).
+ * Reads of entries whose updates are waiting return the entry without them. */
+int ecrm_recovery_begin(ecrm_ctx *ctx, uint32_t server, uint32_t chunks, uint64_t *buf_keys, float *buf_grads,
+                        uint64_t capacity, void *hip_stream);
+int ecrm_recovery_lock(ecrm_ctx *ctx);
+int ecrm_recovery_decode(ecrm_ctx *ctx, void *hip_stream);
+int ecrm_recovery_unlock(ecrm_ctx *ctx, void *hip_stream);
+int ecrm_recovery_state(ecrm_ctx *ctx, void *hip_stream, uint32_t *active, uint32_t *next_chunk, uint32_t *chunks,
+                        uint64_t *buffered);
+
 /* Waits for the stream, then returns ECRM_OK, or EKEYRANGE if any batch since the last
- * ecrm_clear_status (or bind) carried a bad key, or EHIP if the runtime reports an error. */
+ * ecrm_clear_status (or bind) carried a bad key, EBUFFER if one overflowed the recovery buffer, or
+ * EHIP if the runtime reports an error. */
 int ecrm_status(ecrm_ctx *ctx, void *hip_stream);
 int ecrm_clear_status(ecrm_ctx *ctx, void *hip_stream);
 

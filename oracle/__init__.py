@@ -35,6 +35,7 @@ def lib():
         _lib.ecrm_oracle_load.restype = C.c_int
         _lib.ecrm_oracle_max_threads.restype = C.c_int
         _lib.ecrm_oracle_recover_server.restype = C.c_int
+        _lib.ecrm_oracle_recover_range.restype = C.c_int
         _lib.ecrm_oracle_update_rule.restype = C.c_int
         _lib.ecrm_oracle_fail_server.restype = C.c_int
         _lib.ecrm_oracle_degraded_read.restype = C.c_int
@@ -103,6 +104,15 @@ def recover_server(E, A, PE, PA, k: int, S: int, server: int) -> None:
                                           C.c_uint32(k), C.c_uint32(S), C.c_uint32(server))
     if rc != 0:
         raise ValueError("bad server")
+
+
+def recover_range(E, A, PE, PA, k: int, S: int, server: int, g_lo: int, g_hi: int) -> None:
+    R, D = E.shape
+    rc = lib().ecrm_oracle_recover_range(_f32(E), _f32(A), _f32(PE), _f32(PA), C.c_uint64(R), C.c_uint32(D),
+                                         C.c_uint32(k), C.c_uint32(S), C.c_uint32(server), C.c_uint64(g_lo),
+                                         C.c_uint64(g_hi))
+    if rc != 0:
+        raise ValueError("bad server or range")
 
 
 def fail_server(E, A, PE, PA, k: int, S: int, server: int) -> None:

@@ -136,6 +136,20 @@ static int unit_held(uint64_t g, uint32_t k, uint32_t S, uint32_t server)
     return -1;
 }
 
+/* stripes [g_lo, g_hi) only: the unit of work of a recovery that proceeds chunk by chunk (Sec. 3.4) */
+int ecrm_oracle_recover_range(float *E, float *A, float *PE, float *PA, uint64_t R, uint32_t D, uint32_t k,
+                              uint32_t S, uint32_t server, uint64_t g_lo, uint64_t g_hi)
+{
+    if (server >= S || g_hi > R / k) return -1;
+    for (uint64_t g = g_lo; g < g_hi; ++g) {
+        const int u = unit_held(g, k, S, server);
+        if (u < 0) continue;
+        rebuild_unit(E, PE, g, D, k, (uint32_t)u);
+        rebuild_unit(A, PA, g, D, k, (uint32_t)u);
+    }
+    return 0;
+}
+
 int ecrm_oracle_recover_server(float *E, float *A, float *PE, float *PA, uint64_t R, uint32_t D, uint32_t k,
                                uint32_t S, uint32_t server)
 {

@@ -1,0 +1,93 @@
+"""Training while a failed server is rebuilt -- the protocol of Sec. 3.4 ("Training during
+recovery") of the ECRM paper, stated plainly on the CPU (test infrastructure).
+
+The paper: the recovery process locks a fraction of the lost entries; while the lock is held, all
+updates to entries that will be used in recovery of the locked chunk are buffered; when the lock is
+released the buffered updates are applied and the next chunk is locked; training never pauses.
+Readings taken here (the paper does not spell them out):
+  * a chunk is a contiguous range of stripes; "entries used in recovery of the chunk" are all entries
+    (and the parity) of the chunk's stripes that have a unit on the failed server;
+  * an update to an entry that the failed server held cannot be applied before that entry has been
+    rebuilt: it is buffered until its chunk is released, whether or not the chunk is locked;
+  * buffered updates are replayed in arrival order; their load is counted when they are applied;
+  * a batch whose buffered part does not fit the buffer is rejected as a whole.
+All arithmetic is the oracle's (oracle.update / oracle.update_rule / oracle.recover_range).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+
+
+class RecoverySession:
+    def __init__(self, E, A, PE, PA, k, S, lr, eps, server, chunks, capacity, load_data=None, load_parity=None,
+                 optimizer=0, momentum=0.0, combine=0, threads=1):
+        self.E, self.A, self.PE, self.PA = E, A, PE, PA
+        self.k, self.S, self.lr, self.eps = k, S, lr, eps
+        self.optimizer, self.momentum, self.combine, self.threads = optimizer, momentum, combine, threads
+        self.ld, self.lp = load_data, load_parity
+        self.server, self.capacity = server, capacity
+        stripes = E.shape[0] // k
+        self.spc = -(-stripes // chunks)                    # stripes per chunk
+        self.chunks = -(-stripes // self.spc)
+        self.next, self.locked, self.active = 0, False, True
+        self.buf_keys, self.buf_grads = np.zeros(0, np.uint64), np.zeros((0, E.shape[1]), np.float32)
+
+    # -- which updates have to wait ---------------------------------------------------------------
+    def held(self, keys):
+        if not self.active:
+            return np.zeros(len(keys), bool)
+        k, S, s = np.uint64(self.k), np.uint64(self.S), np.uint64(self.server)
+        g, j = keys // k, keys % k
+        parity_here = g % S == s
+        member_here = (s + S - (g + np.uint64(1)) % S) % S          # the j with (g+1+j) mod S == s, if < k
+        affected = parity_here | (member_here < k)
+        chunk = g // np.uint64(self.spc)
+        own_entry_lost = (~parity_here) & (member_here == j)
+        in_locked = (chunk == np.uint64(self.next)) & self.locked
+        return affected & (chunk >= np.uint64(self.next)) & (in_locked | own_entry_lost)
+
+    def _apply(self, keys, grads):
+        if len(keys) == 0:
+            return
+        if self.optimizer == 0 and self.combine == 0:
+            oracle.update(self.E, self.A, self.PE, self.PA, self.k, self.S, self.lr, self.eps, keys, grads,
+                          self.ld, self.lp, threads=self.threads)
+        else:
+            oracle.update_rule(self.E, self.A, self.PE, self.PA, self.k, self.S, self.lr, self.eps, self.momentum,
+                               self.optimizer, self.combine, keys, grads, self.ld, self.lp)
+
+    def update(self, keys, grads):
+        """Returns False (and changes nothing) if the part that has to wait does not fit the buffer."""
+        h = self.held(keys)
+        if len(self.buf_keys) + int(h.sum()) > self.capacity:
+            return False
+        self.buf_keys = np.concatenate([self.buf_keys, keys[h]])
+        self.buf_grads = np.concatenate([self.buf_grads, grads[h]])
+        self._apply(np.ascontiguousarray(keys[~h]), np.ascontiguousarray(grads[~h]))
+        return True
+
+    # -- the recovery process ---------------------------------------------------------------------
+    def lock(self):
+        assert self.active and not self.locked and self.next < self.chunks
+        self.locked = True
+
+    def decode(self):
+        assert self.locked
+        stripes = self.E.shape[0] // self.k
+        lo = self.next * self.spc
+        oracle.recover_range(self.E, self.A, self.PE, self.PA, self.k, self.S, self.server, lo,
+                             min(lo + self.spc, stripes))
+
+    def unlock(self):
+        assert self.locked
+        self.locked = False
+        self.next += 1
+        keys, grads = self.buf_keys, self.buf_grads
+        self.buf_keys, self.buf_grads = keys[:0], grads[:0]
+        ok = self.update(keys, grads)                       # what still has to wait goes back into the buffer
+        assert ok
+        if self.next >= self.chunks:
+            self.active = False
+            assert len(self.buf_keys) == 0

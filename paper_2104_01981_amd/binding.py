@@ -10,6 +10,7 @@ import ctypes as C
 import os
 
 ECRM_OK, ECRM_EINVAL, ECRM_ENOTBOUND, ECRM_ESCRATCH, ECRM_EBATCH, ECRM_EKEYRANGE, ECRM_EHIP = 0, -1, -2, -3, -4, -5, -6
+ECRM_EBUFFER, ECRM_ESTATE = -7, -8
 ECRM_PHASES = 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -19,7 +20,9 @@ _lib = None
 SYMBOLS = ["ecrm_create", "ecrm_destroy", "ecrm_data_bytes", "ecrm_parity_bytes", "ecrm_scratch_bytes",
            "ecrm_bind", "ecrm_encode", "ecrm_route", "ecrm_update", "ecrm_status", "ecrm_clear_status",
            "ecrm_profile", "ecrm_profile_read", "ecrm_batch_stats", "ecrm_strerror",
-           "ecrm_fail_server", "ecrm_recover_server", "ecrm_degraded_read"]
+           "ecrm_fail_server", "ecrm_recover_server", "ecrm_degraded_read",
+           "ecrm_recovery_begin", "ecrm_recovery_lock", "ecrm_recovery_decode", "ecrm_recovery_unlock",
+           "ecrm_recovery_state"]
 
 
 class EcrmConfig(C.Structure):
@@ -59,6 +62,12 @@ def load_library():
         lib.ecrm_fail_server.argtypes = [vp, C.c_uint32, vp]
         lib.ecrm_recover_server.argtypes = [vp, C.c_uint32, vp]
         lib.ecrm_degraded_read.argtypes = [vp, u64p, C.c_uint64, C.c_uint32, f32p, f32p, vp]
+        lib.ecrm_recovery_begin.argtypes = [vp, C.c_uint32, C.c_uint32, u64p, f32p, C.c_uint64, vp]
+        lib.ecrm_recovery_lock.argtypes = [vp]
+        lib.ecrm_recovery_decode.argtypes = [vp, vp]
+        lib.ecrm_recovery_unlock.argtypes = [vp, vp]
+        lib.ecrm_recovery_state.argtypes = [vp, vp, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
+                                            C.POINTER(C.c_uint32), C.POINTER(C.c_uint64)]
         lib.ecrm_status.argtypes = [vp, vp]
         lib.ecrm_clear_status.argtypes = [vp, vp]
         lib.ecrm_profile.argtypes = [vp, C.c_int]
@@ -176,6 +185,39 @@ class Ecrm:
         if check and rc != ECRM_OK:
             raise EcrmError(rc, "ecrm_degraded_read")
         return rc
+
+    def recovery_begin(self, server, chunks, buf_keys, buf_grads, capacity, stream=None, check=True):
+        rc = self._lib.ecrm_recovery_begin(self._ctx, C.c_uint32(server), C.c_uint32(chunks), _ptr(buf_keys),
+                                           _ptr(buf_grads), C.c_uint64(capacity), _stream(stream))
+        if check and rc != ECRM_OK:
+            raise EcrmError(rc, "ecrm_recovery_begin")
+        self._keep_rec = (buf_keys, buf_grads)
+        return rc
+
+    def recovery_lock(self, check=True):
+        rc = self._lib.ecrm_recovery_lock(self._ctx)
+        if check and rc != ECRM_OK:
+            raise EcrmError(rc, "ecrm_recovery_lock")
+        return rc
+
+    def recovery_decode(self, stream=None, check=True):
+        rc = self._lib.ecrm_recovery_decode(self._ctx, _stream(stream))
+        if check and rc != ECRM_OK:
+            raise EcrmError(rc, "ecrm_recovery_decode")
+        return rc
+
+    def recovery_unlock(self, stream=None, check=True):
+        rc = self._lib.ecrm_recovery_unlock(self._ctx, _stream(stream))
+        if check and rc != ECRM_OK:
+            raise EcrmError(rc, "ecrm_recovery_unlock")
+        return rc
+
+    def recovery_state(self, stream=None):
+        a, nx, ch, bf = C.c_uint32(0), C.c_uint32(0), C.c_uint32(0), C.c_uint64(0)
+        rc = self._lib.ecrm_recovery_state(self._ctx, _stream(stream), C.byref(a), C.byref(nx), C.byref(ch), C.byref(bf))
+        if rc != ECRM_OK:
+            raise EcrmError(rc, "ecrm_recovery_state")
+        return dict(active=bool(a.value), next_chunk=int(nx.value), chunks=int(ch.value), buffered=int(bf.value))
 
     def status(self, stream=None):
         return self._lib.ecrm_status(self._ctx, _stream(stream))

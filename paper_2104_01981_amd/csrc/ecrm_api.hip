@@ -23,6 +23,12 @@ struct ecrm_ctx {
     Scratch s;
     int grid_blocks;          // 8 blocks of 256 threads per CU, for the streaming kernels
     int cus;
+    // recovery in progress (host-side state machine; the device sees it as a RecoveryView per call)
+    RecoveryView rv;
+    uint32_t rec_chunks;
+    unsigned long long *buf_keys[2];
+    float *buf_grads[2];
+    uint32_t buf_cap, buf_cur;
     // profiling
     bool profiling;
     hipEvent_t ev[ECRM_PROFILE_MAX_CALLS][ECRM_PHASES + 1];
@@ -62,6 +68,8 @@ const char *ecrm_strerror(int code)
         case ECRM_EBATCH: return "batch larger than max_batch";
         case ECRM_EKEYRANGE: return "a key was >= rows; that batch was not applied";
         case ECRM_EHIP: return "HIP runtime error";
+        case ECRM_EBUFFER: return "recovery buffer full; that batch was not applied";
+        case ECRM_ESTATE: return "call not allowed in the current recovery state";
         default: return "unknown error";
     }
 }
@@ -171,7 +179,7 @@ static int check_launch()
 static void init_if_needed(ecrm_ctx *c, hipStream_t st)
 {
     if (c->need_init) {
-        launch_reset(c->s, c->geo.S, true, st);
+        launch_reset(c->s, c->geo.S, 0, true, st);
         c->need_init = false;
     }
 }
@@ -196,24 +204,24 @@ int ecrm_route(ecrm_ctx *c, const uint64_t *keys, uint64_t n, uint64_t *stripe, 
     return check_launch();
 }
 
-int ecrm_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uint64_t n, void *stream)
+// One batch through the whole pipeline.  During a recovery, held-back items are appended to
+// buf[target] (and the key space gets one more value, `rows`, for them to sort behind the rest).
+static int run_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uint32_t n32, uint32_t target,
+                      hipStream_t st)
 {
-    if (!c) return ECRM_EINVAL;
-    if (!c->bound) return ECRM_ENOTBOUND;
-    if (n > c->max_batch) return ECRM_EBATCH;
-    if (n == 0) return ECRM_OK;
-    if (!aligned(keys, 8) || !aligned(grads, 16)) return ECRM_EINVAL;
-    hipStream_t st = (hipStream_t)stream;
-    const uint32_t n32 = (uint32_t)n;
-
     hipEvent_t *ev = nullptr;
     if (c->profiling && c->ev_calls < ECRM_PROFILE_MAX_CALLS) ev = c->ev[c->ev_calls++];
 
-    launch_reset(c->s, c->geo.S, c->need_init, st);
+    launch_reset(c->s, c->geo.S, n32, c->need_init, st);
     c->need_init = false;
     if (ev) (void)hipEventRecord(ev[0], st);
+    int key_bits = c->key_bits;
+    if (c->rv.active)
+        while (key_bits < 32 && (1ull << key_bits) <= c->cfg.rows) ++key_bits;
     uint32_t *sk = nullptr, *si = nullptr;
-    launch_sort(c->s, c->geo, keys, n32, c->key_bits, &sk, &si, st);
+    launch_sort(c->s, c->geo, c->rv, keys, n32, key_bits, &sk, &si, st);
+    if (c->rv.active)
+        launch_hold_back(c->s, c->geo, c->rv, keys, grads, n32, c->buf_keys[target], c->buf_grads[target], c->buf_cap, st);
     if (ev) (void)hipEventRecord(ev[1], st);
     launch_chains(c->s, c->geo, c->A, grads, sk, si, n32, c->max_slots, c->max_pieces, c->cus, st);
     if (ev) (void)hipEventRecord(ev[2], st);
@@ -221,6 +229,99 @@ int ecrm_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uint64_t 
                  c->cus, st);
     if (ev) (void)hipEventRecord(ev[3], st);
     return check_launch();
+}
+
+int ecrm_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uint64_t n, void *stream)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!c->bound) return ECRM_ENOTBOUND;
+    if (n > c->max_batch) return ECRM_EBATCH;
+    if (n == 0) return ECRM_OK;
+    if (!aligned(keys, 8) || !aligned(grads, 16)) return ECRM_EINVAL;
+    return run_update(c, keys, grads, (uint32_t)n, c->buf_cur, (hipStream_t)stream);
+}
+
+int ecrm_recovery_begin(ecrm_ctx *c, uint32_t server, uint32_t chunks, uint64_t *buf_keys, float *buf_grads,
+                        uint64_t capacity, void *stream)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!c->bound) return ECRM_ENOTBOUND;
+    if (c->rv.active) return ECRM_ESTATE;
+    const uint32_t stripes = c->geo.rows / c->geo.k;
+    if (server >= c->geo.S || chunks < 1 || chunks > stripes) return ECRM_EINVAL;
+    if (capacity < 1 || capacity > c->max_batch || !aligned(buf_keys, 8) || !aligned(buf_grads, 16)) return ECRM_EINVAL;
+    c->rv.active = 1;
+    c->rv.server = server;
+    c->rv.next = 0;
+    c->rv.locked = 0;
+    c->rv.stripes_per_chunk = (stripes + chunks - 1) / chunks;
+    c->rec_chunks = (stripes + c->rv.stripes_per_chunk - 1) / c->rv.stripes_per_chunk;
+    c->buf_cap = (uint32_t)capacity;
+    c->buf_cur = 0;
+    c->buf_keys[0] = (unsigned long long *)buf_keys;
+    c->buf_keys[1] = (unsigned long long *)buf_keys + capacity;
+    c->buf_grads[0] = buf_grads;
+    c->buf_grads[1] = buf_grads + capacity * c->geo.D;
+    init_if_needed(c, (hipStream_t)stream);
+    launch_set_buf_count(c->s, 0, (hipStream_t)stream);
+    return check_launch();
+}
+
+int ecrm_recovery_lock(ecrm_ctx *c)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!c->rv.active || c->rv.locked || c->rv.next >= c->rec_chunks) return ECRM_ESTATE;
+    c->rv.locked = 1;
+    return ECRM_OK;
+}
+
+int ecrm_recovery_decode(ecrm_ctx *c, void *stream)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!c->rv.active || !c->rv.locked) return ECRM_ESTATE;
+    const uint32_t stripes = c->geo.rows / c->geo.k;
+    const uint32_t lo = c->rv.next * c->rv.stripes_per_chunk;
+    const uint32_t hi = lo + c->rv.stripes_per_chunk < stripes ? lo + c->rv.stripes_per_chunk : stripes;
+    launch_recover_range(c->geo, c->E, c->A, c->PE, c->PA, c->rv.server, lo, hi, c->grid_blocks, (hipStream_t)stream);
+    return check_launch();
+}
+
+int ecrm_recovery_unlock(ecrm_ctx *c, void *stream)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!c->rv.active || !c->rv.locked) return ECRM_ESTATE;
+    hipStream_t st = (hipStream_t)stream;
+    // how much is waiting: the only synchronisation of the recovery protocol
+    if (hipStreamSynchronize(st) != hipSuccess) return ECRM_EHIP;
+    Header h;
+    if (hipMemcpy(&h, c->s.hdr, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return ECRM_EHIP;
+    c->rv.locked = 0;
+    c->rv.next += 1;
+    const uint32_t waiting = h.buf_count;
+    const uint32_t src = c->buf_cur;
+    c->buf_cur ^= 1u;                               // what still has to wait is re-appended to the other half
+    launch_set_buf_count(c->s, 0, st);
+    int rc = check_launch();
+    if (rc == ECRM_OK && waiting)
+        rc = run_update(c, (const uint64_t *)c->buf_keys[src], c->buf_grads[src], waiting, c->buf_cur, st);
+    if (c->rv.next >= c->rec_chunks) c->rv.active = 0;       // every chunk is rebuilt, nothing can be waiting any more
+    return rc;
+}
+
+int ecrm_recovery_state(ecrm_ctx *c, void *stream, uint32_t *active, uint32_t *next_chunk, uint32_t *chunks,
+                        uint64_t *buffered)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!c->bound) return ECRM_ENOTBOUND;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return ECRM_EHIP;
+    Header h;
+    memset(&h, 0, sizeof(h));
+    if (!c->need_init && hipMemcpy(&h, c->s.hdr, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return ECRM_EHIP;
+    if (active) *active = c->rv.active;
+    if (next_chunk) *next_chunk = c->rv.next;
+    if (chunks) *chunks = c->rec_chunks;
+    if (buffered) *buffered = h.buf_count;
+    return ECRM_OK;
 }
 
 int ecrm_fail_server(ecrm_ctx *c, uint32_t server, void *stream)
@@ -264,7 +365,8 @@ int ecrm_status(ecrm_ctx *c, void *stream)
     Header h;
     if (hipMemcpy(&h, c->s.hdr, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return ECRM_EHIP;
     if (hipGetLastError() != hipSuccess) return ECRM_EHIP;
-    return h.err_sticky ? ECRM_EKEYRANGE : ECRM_OK;
+    if (h.err_sticky & 1u) return ECRM_EKEYRANGE;
+    return (h.err_sticky & 2u) ? ECRM_EBUFFER : ECRM_OK;
 }
 
 int ecrm_clear_status(ecrm_ctx *c, void *stream)

@@ -36,7 +36,11 @@ struct Header {
     uint32_t n_long;       // rows on the split-chain path in this batch
     uint32_t n_pieces;     // chain pieces in this batch
     unsigned long long n_long_items;
-    uint32_t pad[58];
+    uint32_t n_valid;      // items of the batch that are applied now; the rest (held back during a recovery)
+                           // carry the row id `rows` and sort behind them
+    uint32_t n_held;       // items of the batch held back
+    uint32_t buf_count;    // held-back items waiting in the buffer (all batches)
+    uint32_t pad[55];
 };
 static_assert(sizeof(Header) == 256, "header is one 256-byte block");
 
@@ -54,6 +58,30 @@ struct Scratch {           // device pointers carved out of the caller's scratch
     double *long_res;              // [max_slots][2][D]: sum of steps, final accumulator
 };
 
+// What an update has to know about a recovery in progress (Sec. 3.4): stripes are split into
+// `chunks` equal ranges; chunks below `next` are rebuilt, chunk `next` is being rebuilt if `locked`.
+// An update is held back (buffered) if its stripe is in the locked chunk, or if its own entry is
+// the unit the failed server held and has not been rebuilt yet.
+struct RecoveryView {
+    uint32_t active, server, next, locked;
+    uint32_t stripes_per_chunk;
+};
+__host__ __device__ __forceinline__ bool held_back(const RecoveryView &r, uint32_t x, uint32_t k, uint32_t S)
+{
+    if (!r.active) return false;
+    const uint32_t g = x / k, j = x - g * k;
+    const uint32_t p = g % S;
+    uint32_t lost = k;                                // unit of stripe g on the failed server: k = its parity
+    if (p != r.server) {
+        lost = (r.server + S - (p + 1u) % S) % S;     // (g+1+lost) mod S == server
+        if (lost >= k) return false;                  // the stripe has nothing on the failed server
+    }
+    const uint32_t c = g / r.stripes_per_chunk;
+    if (c < r.next) return false;                     // already rebuilt
+    if (c == r.next && r.locked) return true;         // being rebuilt right now
+    return lost == j;                                 // not rebuilt yet: only the lost entry itself waits
+}
+
 struct Geometry {
     uint32_t D, k, S;
     uint32_t rows;         // R (< 2^32)
@@ -65,9 +93,15 @@ struct Geometry {
 };
 
 // ---- launchers (each checks nothing: the API layer validates shapes before calling) -------------
-void launch_reset(const Scratch &s, uint32_t S, bool clear_sticky, hipStream_t st);
-void launch_sort(const Scratch &s, const Geometry &g, const uint64_t *keys, uint32_t n, int key_bits,
-                 uint32_t **sorted_keys, uint32_t **sorted_vals, hipStream_t st);
+void launch_reset(const Scratch &s, uint32_t S, uint32_t n, bool clear_sticky, hipStream_t st);
+void launch_sort(const Scratch &s, const Geometry &g, const RecoveryView &rv, const uint64_t *keys, uint32_t n,
+                 int key_bits, uint32_t **sorted_keys, uint32_t **sorted_vals, hipStream_t st);
+void launch_hold_back(const Scratch &s, const Geometry &g, const RecoveryView &rv, const uint64_t *keys,
+                      const float *grads, uint32_t n, unsigned long long *buf_keys, float *buf_grads,
+                      uint32_t buf_cap, hipStream_t st);
+void launch_recover_range(const Geometry &g, float *E, float *A, float *PE, float *PA, uint32_t server,
+                          uint32_t g_lo, uint32_t g_hi, int grid_blocks, hipStream_t st);
+void launch_set_buf_count(const Scratch &s, uint32_t count, hipStream_t st);
 void launch_chains(const Scratch &s, const Geometry &g, const float *A, const float *grads,
                    const uint32_t *sk, const uint32_t *si, uint32_t n, uint32_t max_slots,
                    uint32_t max_pieces, int cus, hipStream_t st);

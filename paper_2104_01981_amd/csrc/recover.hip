@@ -83,11 +83,12 @@ __device__ __forceinline__ void rebuild_row(float *T, float *P, uint32_t g, int 
     }
 }
 
-__global__ __launch_bounds__(256) void recover_server_kernel(float *E, float *A, float *PE, float *PA, uint32_t stripes,
-                                                             uint32_t D, uint32_t k, uint32_t S, uint32_t server)
+// stripes [g_lo, g_hi)
+__global__ __launch_bounds__(256) void recover_server_kernel(float *E, float *A, float *PE, float *PA, uint32_t g_lo,
+                                                             uint32_t g_hi, uint32_t D, uint32_t k, uint32_t S, uint32_t server)
 {
     const uint32_t w0 = (blockIdx.x * blockDim.x + threadIdx.x) / kWave, nw = (gridDim.x * blockDim.x) / kWave;
-    for (uint32_t g = w0; g < stripes; g += nw) {
+    for (uint32_t g = g_lo + w0; g < g_hi; g += nw) {
         const int u = unit_on_server(g, k, S, server);
         if (u < 0) continue;
         rebuild_row(E, PE, g, u, D, k);
@@ -146,7 +147,14 @@ void launch_fail_server(const Geometry &g, float *E, float *A, float *PE, float 
 void launch_recover_server(const Geometry &g, float *E, float *A, float *PE, float *PA, uint32_t server,
                            int grid_blocks, hipStream_t st)
 {
-    hipLaunchKernelGGL(recover_server_kernel, dim3(grid_blocks), dim3(256), 0, st, E, A, PE, PA, g.rows / g.k, g.D, g.k, g.S,
+    launch_recover_range(g, E, A, PE, PA, server, 0, g.rows / g.k, grid_blocks, st);
+}
+
+void launch_recover_range(const Geometry &g, float *E, float *A, float *PE, float *PA, uint32_t server,
+                          uint32_t g_lo, uint32_t g_hi, int grid_blocks, hipStream_t st)
+{
+    if (g_lo >= g_hi) return;
+    hipLaunchKernelGGL(recover_server_kernel, dim3(grid_blocks), dim3(256), 0, st, E, A, PE, PA, g_lo, g_hi, g.D, g.k, g.S,
                        server);
 }
 

@@ -43,7 +43,7 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *s_wave
     return off + incl - v;
 }
 
-__global__ void reset_kernel(Header *h, unsigned long long *cnt, uint32_t S, int clear_sticky)
+__global__ void reset_kernel(Header *h, unsigned long long *cnt, uint32_t S, uint32_t n, int clear_sticky)
 {
     const uint32_t t = threadIdx.x;
     if (t == 0) {
@@ -51,7 +51,12 @@ __global__ void reset_kernel(Header *h, unsigned long long *cnt, uint32_t S, int
         h->n_long = 0;
         h->n_pieces = 0;
         h->n_long_items = 0;
-        if (clear_sticky) h->err_sticky = 0;
+        h->n_valid = n;
+        h->n_held = 0;
+        if (clear_sticky) {
+            h->err_sticky = 0;
+            h->buf_count = 0;
+        }
     }
     for (uint32_t i = t; i < 2 * S; i += blockDim.x) cnt[i] = 0;
 }
@@ -61,12 +66,17 @@ __global__ void clear_status_kernel(Header *h)
     if (threadIdx.x == 0) h->err_sticky = 0;
 }
 
+__global__ void set_buf_count_kernel(Header *h, uint32_t count)
+{
+    if (threadIdx.x == 0) h->buf_count = count;
+}
+
 // ---- histogram ---------------------------------------------------------------------------------
 // FIRST: keys are the caller's u64 row ids; also range check + load accounting.
 template <bool FIRST>
 __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
     const void *keys_in, uint32_t n, uint32_t nblocks, int shift, int bits, uint32_t *block_hist,
-    Header *hdr, unsigned long long *cnt, uint32_t rows, uint32_t k, uint32_t S)
+    Header *hdr, unsigned long long *cnt, uint32_t rows, uint32_t k, uint32_t S, uint32_t S_place, RecoveryView rv)
 {
     __shared__ uint32_t s_hist[kMaxBins];
     __shared__ uint32_t s_cnt[2 * 1024];
@@ -92,6 +102,8 @@ __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
                 key = (uint32_t)k64;
                 if (k64 >= (uint64_t)rows) {
                     bad = true;
+                } else if (held_back(rv, key, k, S_place)) {
+                    key = rows;                                   // held back: sorts behind every row, not applied
                 } else if (S) {                                   // S == 0: the caller counts per distinct row later
                     const uint32_t g = key / k, j = key - g * k;
                     atomicAdd(&s_cnt[(g + 1 + j) % S], 1u);       // server of the entry
@@ -141,7 +153,8 @@ __global__ __launch_bounds__(kSortThreads) void sort_scan_kernel(uint32_t *block
 template <bool FIRST>
 __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_kernel(
     const void *keys_in, const uint32_t *vals_in, uint32_t *keys_out, uint32_t *vals_out,
-    const uint32_t *block_hist, const uint32_t *bin_total, uint32_t n, uint32_t nblocks, int shift, int bits)
+    const uint32_t *block_hist, const uint32_t *bin_total, uint32_t n, uint32_t nblocks, int shift, int bits,
+    uint32_t rows, uint32_t k, uint32_t S_place, RecoveryView rv)
 {
     __shared__ uint32_t s_keys[kSortTile];
     __shared__ uint32_t s_vals[kSortTile];
@@ -164,7 +177,9 @@ __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_ke
         val[r] = 0;
         if (i < n) {
             if (FIRST) {
-                key[r] = (uint32_t)((const uint64_t *)keys_in)[i];
+                const uint64_t k64 = ((const uint64_t *)keys_in)[i];
+                key[r] = (uint32_t)k64;
+                if (k64 < (uint64_t)rows && held_back(rv, key[r], k, S_place)) key[r] = rows;
                 val[r] = i;
             } else {
                 key[r] = ((const uint32_t *)keys_in)[i];
@@ -239,9 +254,14 @@ __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_ke
 }
 
 // ---- host side -------------------------------------------------------------------------------------
-void launch_reset(const Scratch &s, uint32_t S, bool clear_sticky, hipStream_t st)
+void launch_reset(const Scratch &s, uint32_t S, uint32_t n, bool clear_sticky, hipStream_t st)
 {
-    hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, st, s.hdr, s.cnt, S, clear_sticky ? 1 : 0);
+    hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, st, s.hdr, s.cnt, S, n, clear_sticky ? 1 : 0);
+}
+
+void launch_set_buf_count(const Scratch &s, uint32_t count, hipStream_t st)
+{
+    hipLaunchKernelGGL(set_buf_count_kernel, dim3(1), dim3(64), 0, st, s.hdr, count);
 }
 
 void launch_clear_status(const Scratch &s, hipStream_t st)
@@ -249,8 +269,8 @@ void launch_clear_status(const Scratch &s, hipStream_t st)
     hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, st, s.hdr);
 }
 
-void launch_sort(const Scratch &s, const Geometry &g, const uint64_t *keys, uint32_t n, int key_bits,
-                 uint32_t **sorted_keys, uint32_t **sorted_vals, hipStream_t st)
+void launch_sort(const Scratch &s, const Geometry &g, const RecoveryView &rv, const uint64_t *keys, uint32_t n,
+                 int key_bits, uint32_t **sorted_keys, uint32_t **sorted_vals, hipStream_t st)
 {
     const uint32_t nblocks = (n + kSortTile - 1) / kSortTile;
     int passes = (key_bits + kMaxRadixBits - 1) / kMaxRadixBits;
@@ -265,22 +285,22 @@ void launch_sort(const Scratch &s, const Geometry &g, const uint64_t *keys, uint
         if (p == 0) {
             hipLaunchKernelGGL(sort_hist_kernel<true>, dim3(nblocks), dim3(kSortThreads), 0, st,
                                (const void *)keys, n, nblocks, shift, bits, s.block_hist, s.hdr, s.cnt,
-                               g.rows, g.k, (g.mode & 2u) ? 0u : g.S);
+                               g.rows, g.k, (g.mode & 2u) ? 0u : g.S, g.S, rv);
             hipLaunchKernelGGL(sort_scan_kernel, dim3(bins), dim3(kSortThreads), 0, st, s.block_hist,
                                s.bin_total, nblocks);
             hipLaunchKernelGGL(sort_scatter_kernel<true>, dim3(nblocks), dim3(kSortThreads), 0, st,
                                (const void *)keys, (const uint32_t *)nullptr, s.keys[0], s.vals[0],
-                               s.block_hist, s.bin_total, n, nblocks, shift, bits);
+                               s.block_hist, s.bin_total, n, nblocks, shift, bits, g.rows, g.k, g.S, rv);
             cur = 0;
         } else {
             hipLaunchKernelGGL(sort_hist_kernel<false>, dim3(nblocks), dim3(kSortThreads), 0, st,
                                (const void *)s.keys[cur], n, nblocks, shift, bits, s.block_hist, s.hdr,
-                               s.cnt, g.rows, g.k, g.S);
+                               s.cnt, g.rows, g.k, g.S, g.S, rv);
             hipLaunchKernelGGL(sort_scan_kernel, dim3(bins), dim3(kSortThreads), 0, st, s.block_hist,
                                s.bin_total, nblocks);
             hipLaunchKernelGGL(sort_scatter_kernel<false>, dim3(nblocks), dim3(kSortThreads), 0, st,
                                (const void *)s.keys[cur], s.vals[cur], s.keys[cur ^ 1], s.vals[cur ^ 1],
-                               s.block_hist, s.bin_total, n, nblocks, shift, bits);
+                               s.block_hist, s.bin_total, n, nblocks, shift, bits, g.rows, g.k, g.S, rv);
             cur ^= 1;
         }
         shift += bits;

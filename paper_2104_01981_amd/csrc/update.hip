@@ -181,6 +181,7 @@ __global__ __launch_bounds__(256) void long_find_kernel(const uint32_t *sk, uint
                                                         uint32_t max_slots)
 {
     if (hdr->batch_bad) return;
+    n = min(n, hdr->n_valid);
     const uint32_t stride = gridDim.x * blockDim.x;
     for (uint32_t p = blockIdx.x * blockDim.x + threadIdx.x; p + kLongRun < n; p += stride) {
         const uint32_t x = sk[p];
@@ -202,6 +203,7 @@ __global__ __launch_bounds__(256) void long_plan_kernel(const uint32_t *sk, uint
                                                         uint32_t max_slots, uint32_t max_pieces)
 {
     if (hdr->batch_bad) return;
+    n = min(n, hdr->n_valid);
     const uint32_t nl = min(hdr->n_long, max_slots);
     const uint32_t lane = lane_id();
     for (uint32_t slot = wave_id(); slot < nl; slot += wave_count()) {
@@ -512,9 +514,9 @@ struct ApplyArgs {
 // through memory.  Used when the stripe does not fit the wave's window: runs of more than a few
 // dozen updates, and entries whose totals come from the split-chain path.
 template <int NC, int MODE>
-__device__ __forceinline__ void apply_stripe_general(const ApplyArgs &a, uint32_t pos, uint32_t cb)
+__device__ __forceinline__ void apply_stripe_general(const ApplyArgs &a, uint32_t n, uint32_t pos, uint32_t cb)
 {
-    const uint32_t D = a.geo.D, k = a.geo.k, n = a.n;
+    const uint32_t D = a.geo.D, k = a.geo.k;
     const RuleParams rp = rule_params(a.geo);
     const uint32_t col0 = cb * NC * 128u;
     uint32_t key = uniform(a.sk[pos]);
@@ -761,7 +763,7 @@ __device__ __forceinline__ void apply_stripes_body(const ApplyArgs &a)
             a.load_parity[i] += a.cnt[S + i];
         }
     }
-    const uint32_t n = a.n, k = a.geo.k, lane = lane_id();
+    const uint32_t n = min(a.n, a.hdr->n_valid), k = a.geo.k, lane = lane_id();
     const uint32_t nchunks = (n + kChunk - 1) / kChunk;
     for (uint32_t ch = wave_id(); ch < nchunks; ch += wave_count()) {
         const uint32_t p0 = ch * kChunk;
@@ -785,7 +787,7 @@ __device__ __forceinline__ void apply_stripes_body(const ApplyArgs &a)
         const uint32_t end = last_inside ? (after ? lowest_bit(after) : vend) : last;
         for (uint32_t cb = 0; cb < a.geo.ncb; ++cb) {
             apply_window<NC, MODE>(a, wkey, widx, rowheads, stripeheads, first, end, cb);
-            if (!last_inside) apply_stripe_general<NC, MODE>(a, p0 + last, cb);
+            if (!last_inside) apply_stripe_general<NC, MODE>(a, n, p0 + last, cb);
         }
     }
 }
@@ -809,6 +811,7 @@ __global__ __launch_bounds__(256) void count_rows_kernel(const uint32_t *sk, uin
 {
     __shared__ uint32_t s_cnt[2 * 1024];
     if (hdr->batch_bad) return;
+    n = min(n, hdr->n_valid);
     for (uint32_t i = threadIdx.x; i < 2 * S; i += blockDim.x) s_cnt[i] = 0;
     __syncthreads();
     const uint32_t stride = gridDim.x * blockDim.x;

@@ -1,0 +1,115 @@
+"""Training while a server is rebuilt chunk by chunk (Sec. 3.4): libecrm against the protocol oracle,
+with the decoder on a second stream."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+from ecrm_case import Case, grads_for, log
+from oracle.recovery_session import RecoverySession
+
+pytestmark = pytest.mark.gpu
+
+
+def _batch(seed, first, n, R, D, hot_rows):
+    keys = si.uniform_keys(seed, first, n, R)
+    for i, h in enumerate(hot_rows):                  # a few hot entries, some of them on the failed server
+        keys[i::11] = h
+    return keys, grads_for(seed, first, n, D)
+
+
+@pytest.mark.parametrize("chunks", [1, 4, 10])
+@pytest.mark.parametrize("R,D,k,S,server,opt,comb", [(4 * 3000, 128, 4, 5, 2, 0, 0), (2 * 2500, 128, 2, 5, 0, 0, 0),
+                                                      (10 * 400, 256, 10, 11, 7, 0, 0), (4 * 3000, 128, 4, 5, 4, 1, 0),
+                                                      (4 * 3000, 128, 4, 5, 1, 0, 1)])
+def test_training_during_recovery(chunks, R, D, k, S, server, opt, comb):
+    n, seed = 20000, 83
+    cap = 8 * n                                       # hot lost entries of the last chunk wait through the whole recovery
+    c = Case(R, D, k, S, max_batch=cap, seed=seed, optimizer=opt, momentum=0.9, combine=comb)
+    st, mem, ds, ps = oracle.route(np.arange(R, dtype=np.uint64), R, k, S)
+    lost_rows = np.nonzero(ds == server)[0]
+    hot = [int(lost_rows[3]), int(lost_rows[len(lost_rows) // 2]), 5, int(lost_rows[-1]), R - 1]
+    first = 0
+    for _ in range(2):                                # some training before the failure
+        keys, g = _batch(seed, first, n, R, D, hot)
+        c.update(keys, g)
+        first += n
+    c.ctx.fail_server(server)
+    oracle.fail_server(c.hE, c.hA, c.hPE, c.hPA, k, S, server)
+    buf_keys = torch.empty(2 * cap, dtype=torch.int64, device="cuda")
+    buf_grads = torch.empty(2 * cap, D, device="cuda")
+    c.ctx.recovery_begin(server, chunks, buf_keys, buf_grads, cap)
+    ses = RecoverySession(c.hE, c.hA, c.hPE, c.hPA, k, S, c.lr, c.eps, server, chunks, cap, c.hld, c.hlp,
+                          optimizer=opt, momentum=0.9, combine=comb, threads=8)
+    side = torch.cuda.Stream()
+    main = torch.cuda.current_stream()
+
+    def both_update():
+        nonlocal first
+        keys, g = _batch(seed, first, n, R, D, hot)
+        first += n
+        c.ctx.update(torch.from_numpy(keys.view(np.int64)).cuda(), g)
+        assert ses.update(keys, g.cpu().numpy())
+
+    max_waiting = 0
+    for ch in range(ses.chunks):
+        both_update()
+        c.ctx.recovery_lock()
+        ses.lock()
+        both_update()                                  # enqueued after the lock: its chunk items wait
+        ev = torch.cuda.Event()
+        ev.record(main)
+        side.wait_event(ev)                            # decode after everything enqueued before it ...
+        c.ctx.recovery_decode(stream=side)
+        done = torch.cuda.Event()
+        done.record(side)
+        ses.decode()
+        both_update()                                  # ... and concurrently with this one
+        stt = c.ctx.recovery_state()
+        assert stt["active"] and stt["next_chunk"] == ch and stt["buffered"] == len(ses.buf_keys)
+        max_waiting = max(max_waiting, stt["buffered"])
+        main.wait_event(done)
+        c.ctx.recovery_unlock()
+        ses.unlock()
+    stt = c.ctx.recovery_state()
+    assert not stt["active"] and stt["buffered"] == 0 and max_waiting > 0
+    both_update()
+    log("recovery under load", (chunks, R, D, k, S, server, opt, comb), "max waiting", max_waiting, c.compare("session"))
+    assert not bool(torch.isnan(c.E).any()) and not bool(torch.isnan(c.PA).any())
+    c.check_invariant()
+
+
+def test_recovery_buffer_overflow_and_state_errors():
+    R, D, k, S, n, server = 4 * 1000, 128, 4, 5, 8000, 3
+    c = Case(R, D, k, S, max_batch=n, seed=89)
+    keys = si.uniform_keys(89, 0, n, R)
+    g = grads_for(89, 0, n, D)
+    kt = torch.from_numpy(keys.view(np.int64)).cuda()
+    cap = 64
+    buf_keys = torch.empty(2 * cap, dtype=torch.int64, device="cuda")
+    buf_grads = torch.empty(2 * cap, D, device="cuda")
+    assert c.ctx.recovery_lock(check=False) == -8                  # no recovery in progress
+    assert c.ctx.recovery_begin(9, 2, buf_keys, buf_grads, cap, check=False) == -1
+    assert c.ctx.recovery_begin(server, 0, buf_keys, buf_grads, cap, check=False) == -1
+    assert c.ctx.recovery_begin(server, 2, buf_keys, buf_grads, n + 1, check=False) == -1
+    c.ctx.recovery_begin(server, 2, buf_keys, buf_grads, cap)
+    assert c.ctx.recovery_begin(server, 2, buf_keys, buf_grads, cap, check=False) == -8
+    assert c.ctx.recovery_decode(check=False) == -8                 # nothing locked
+    assert c.ctx.recovery_unlock(check=False) == -8
+    c.ctx.recovery_lock()
+    assert c.ctx.recovery_lock(check=False) == -8
+    before = [t.clone() for t in (c.E, c.A, c.PE, c.PA, c.ld, c.lp)]
+    c.ctx.update(kt, g)                                             # far more than 64 items have to wait
+    assert c.ctx.status() == -7                                     # ECRM_EBUFFER
+    assert c.ctx.batch_stats()["rejected"] == 1
+    for t, b in zip((c.E, c.A, c.PE, c.PA, c.ld, c.lp), before):
+        assert torch.equal(t, b)
+    assert c.ctx.recovery_state()["buffered"] == 0
+    c.ctx.clear_status()
+    # a batch that fits: 10 items of the locked chunk
+    st = keys // np.uint64(k)
+    small = keys[st < 100][:10].copy()
+    c.ctx.update(torch.from_numpy(small.view(np.int64)).cuda(), g[:10].contiguous())
+    assert c.ctx.status() == 0
+    assert 0 < c.ctx.recovery_state()["buffered"] <= 10
