@@ -373,6 +373,42 @@ def main():
         }
         del oe, oa
 
+        # training while server 0 is rebuilt chunk by chunk: the decoder on a second stream, one update
+        # batch enqueued while each chunk is locked, buffered updates replayed at every unlock
+        if args.layout == "arena":
+            buf_keys = torch.empty(2 * per, dtype=torch.int64, device=dev)
+            buf_grads = torch.empty(2 * per, D, device=dev)
+            side, main = torch.cuda.Stream(), torch.cuda.current_stream()
+            under_load = {}
+            for chunks in (1, 10):
+                ctx.recovery_begin(0, chunks, buf_keys, buf_grads, per)
+                torch.cuda.synchronize()
+                tr0 = time.perf_counter()
+                waiting = 0
+                for ch in range(chunks):
+                    ctx.recovery_lock()
+                    ev, done = torch.cuda.Event(), torch.cuda.Event()
+                    ev.record(main)
+                    side.wait_event(ev)
+                    ctx.recovery_decode(stream=side)
+                    done.record(side)
+                    ctx.update(keys[ch % nb], grads[ch % nb])
+                    main.wait_event(done)
+                    waiting = max(waiting, ctx.recovery_state()["buffered"])
+                    ctx.recovery_unlock()
+                torch.cuda.synchronize()
+                tr1 = time.perf_counter()
+                rc_status = ctx.status()
+                under_load[str(chunks)] = {
+                    "recovery_ms": (tr1 - tr0) * 1e3, "updates_applied_meanwhile": chunks * per,
+                    "items_per_s_during_recovery": chunks * per / (tr1 - tr0),
+                    "relative_to_normal": chunks * per / (tr1 - tr0) / value,
+                    "max_updates_waiting": waiting, "status": rc_status}
+                if rc_status != 0:
+                    ctx.clear_status()
+            out["recovery"]["under_load"] = under_load
+            del buf_keys, buf_grads
+
     if not args.no_cpu_baseline:
         import oracle
         threads = min(16, oracle.max_threads())
