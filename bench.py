@@ -60,6 +60,9 @@ def main():
     ap.add_argument("--servers", type=int, default=0, help="servers (default 5)")
     ap.add_argument("--optimizer", default="adagrad", choices=["adagrad", "momentum"])
     ap.add_argument("--combine", action="store_true", help="synchronous variant: one update per modified entry")
+    ap.add_argument("--propagation", default="difference", choices=["difference", "gradient", "none"],
+                    help="how the parities follow: the paper's difference propagation, the gradient-propagation "
+                         "strawman (Sec. 3.3.1), or not at all (training without fault tolerance)")
     ap.add_argument("--resident", type=int, default=0, help="batches kept resident and cycled through (default: all)")
     ap.add_argument("--graph", action="store_true",
                     help="capture each resident batch's ecrm_update in a HIP graph and replay it (small, launch-bound "
@@ -123,13 +126,16 @@ def main():
         variant += "/momentum0.9"
     if args.combine:
         variant += "/combined"
+    if args.propagation != "difference":
+        variant += f"/{args.propagation}-propagation"
+    prop = {"difference": 0, "gradient": 1, "none": 2}[args.propagation]
 
     t_setup = time.perf_counter()
     ctx = Ecrm(R, D, k, S, si.DEFAULT_LR, si.DEFAULT_EPS, per, optimizer=1 if args.optimizer == "momentum" else 0,
-               momentum=0.9 if args.optimizer == "momentum" else 0.0, combine=1 if args.combine else 0)
+               momentum=0.9 if args.optimizer == "momentum" else 0.0, combine=1 if args.combine else 0, propagation=prop)
     # One arena for everything that stays resident (tables, scratch, all batches), carved at 2 MiB.
-    # Order matters on this device: tables that are swept together must start >= 32 GiB apart (see
-    # the design doc), so batches are placed between them.
+    # Order matters on this device: tables that are swept together must start >= 32 GiB apart, so
+    # batches are placed between them.
     ALIGN = 2 << 20
     sizes = {"E": R * D * 4, "A": R * D * 4, "PE": R // k * D * 4, "PA": R // k * D * 4, "ld": S * 8, "lp": S * 8,
              "scratch": ctx.scratch_bytes()}
@@ -180,6 +186,13 @@ def main():
         U = int(uk.numel())
         Up = int(torch.unique(uk // k).numel())
         n_long = int(cnt[cnt > 256].sum())
+        if prop == 2:        # no parities
+            return per * (8 + 4 * D) + U * 16 * D, per * 8 + (per - n_long) * 4 * D + U * 16 * D
+        if prop == 1:        # every gradient goes to two servers; the two apply launches together
+            _, pcnt = torch.unique(kt // k, return_counts=True)
+            n_long_p = int(pcnt[pcnt > 256].sum())
+            return (2 * per * (8 + 4 * D) + (U + Up) * 16 * D,
+                    2 * per * 8 + (2 * per - n_long - n_long_p) * 4 * D + (U + Up) * 16 * D)
         return per * (8 + 4 * D) + (U + Up) * 16 * D, per * 8 + (per - n_long) * 4 * D + (U + Up) * 16 * D
 
     # Physical placement is the driver's; now and then (e.g. right after another process released a
@@ -326,7 +339,8 @@ def main():
         "config": {"workload": f"{args.workload}" + (f">>{sh}" if sh else "") + variant, "items_per_step": per,
                    "rows": R, "dim": D, "k": k, "servers": S, "storage": "f32", "optimizer": args.optimizer, "combine": bool(args.combine),
                    "keys": w["kind"], "batches_resident": nb, "hip_graph": bool(args.graph)},
-        "roofline": {"bound": "hbm", "kernel": "apply_stripes_kernel_d128" if D <= 128 else "apply_stripes_kernel_d256", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": ("apply_stripes_kernel" if prop == 0 else "apply_rows_kernel") + ("_d128" if D <= 128 else "_d256")
+                     + (" (two launches per step)" if prop == 1 else ""), "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(args.workload, sh, variant),
                      "algorithmic_bytes_per_launch": apply_bytes, "avg_launch_ms": apply_ms},
@@ -337,8 +351,17 @@ def main():
                  "frac_of_hbm_peak": path_gbs / HBM_PEAK_GBS},
     }
 
-    if not args.no_recovery:
-        # next row of the scope table: full recovery of one server and degraded reads (Sec. 3.4)
+    # Updates per server over the warm-up and timed calls (Sec. 4.3, effect on load imbalance): entry
+    # updates alone, and entry plus parity updates under the rotating placement.
+    ldh, lph = ld.cpu().double(), lp.cpu().double()
+    out["load_balance"] = {
+        "entry_updates_per_server": [int(v) for v in ldh], "parity_updates_per_server": [int(v) for v in lph],
+        "max_over_min_entries_only": float(ldh.max() / ldh.min()),
+        "max_over_min_with_parities": float((ldh + lph).max() / (ldh + lph).min()),
+    }
+
+    if not args.no_recovery and prop == 0:
+        # full recovery of one server and degraded reads (Sec. 3.4)
         def timed(fn, reps=3):
             fn()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -47,6 +47,18 @@ enum {
 
 enum { ECRM_OPT_ADAGRAD = 0, ECRM_OPT_MOMENTUM = 1 };
 
+/* How the parities follow the entries. */
+enum {
+    ECRM_PROP_DIFFERENCE = 0, /* difference propagation, the paper's method (Sec. 3.3.2)               */
+    ECRM_PROP_GRADIENT = 1,   /* the strawman of Sec. 3.3.1: the gradient itself goes to the parity,
+                                 which applies the optimizer with its own state.  With Adagrad the
+                                 parities stop being the sums of their entries -- kept to show that,
+                                 and what the second pass over the gradients costs (Sec. 4.3
+                                 "Benefit of difference propagation")                                */
+    ECRM_PROP_NONE = 2        /* parities left alone: training without fault tolerance, the baseline
+                                 the overheads of Sec. 4.3 are quoted against                        */
+};
+
 typedef struct {
     uint64_t rows;      /* R: k <= R <= 2^32 - 4096, multiple of k                              */
     uint32_t dim;       /* D: floats per entry, multiple of 4, 4..1024 (the paper uses 128, 256) */
@@ -65,6 +77,9 @@ typedef struct {
                            1: their gradients are summed and applied as ONE update per modified entry,
                            and the load counters count one update per modified entry (the synchronous
                            variant of Sec. 4.4 "Synchronous training")                             */
+    uint32_t propagation; /* ECRM_PROP_*; GRADIENT needs combine = 0.  With GRADIENT the load counters are
+                           those of DIFFERENCE (one entry and one parity update per item); with NONE
+                           load_parity is not touched.  The recovery-under-load calls need DIFFERENCE. */
 } ecrm_config;
 
 /* Validates the configuration and creates a host-side context.  No device memory is touched. */

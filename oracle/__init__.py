@@ -31,6 +31,7 @@ def lib():
         _lib = C.CDLL(_LIB)
         _lib.ecrm_oracle_update.restype = C.c_int
         _lib.ecrm_oracle_update_gradient_propagation.restype = C.c_int
+        _lib.ecrm_oracle_update_gradient_propagation_rule.restype = C.c_int
         _lib.ecrm_oracle_route.restype = C.c_int
         _lib.ecrm_oracle_load.restype = C.c_int
         _lib.ecrm_oracle_max_threads.restype = C.c_int
@@ -175,5 +176,19 @@ def update_gradient_propagation(E, A, PE, PA, k: int, lr: float, eps: float, key
     rc = lib().ecrm_oracle_update_gradient_propagation(
         _f32(E), _f32(A), _f32(PE), _f32(PA), C.c_uint64(R), C.c_uint32(D), C.c_uint32(k),
         C.c_float(lr), C.c_float(eps), _u64(keys), _f32(grads), C.c_uint64(len(keys)))
+    if rc != 0:
+        raise RuntimeError(f"oracle strawman failed ({rc})")
+
+
+def update_gradient_propagation_rule(E, A, PE, PA, k: int, lr: float, eps: float, keys, grads,
+                                     optimizer: int = 0, momentum: float = 0.0) -> None:
+    """Gradient propagation (Sec. 3.3.1) under Adagrad (optimizer 0) or momentum SGD (optimizer 1)."""
+    R, D = E.shape
+    rc = lib().ecrm_oracle_update_gradient_propagation_rule(
+        _f32(E), _f32(A), _f32(PE), _f32(PA), C.c_uint64(R), C.c_uint32(D), C.c_uint32(k),
+        C.c_float(lr), C.c_float(eps), C.c_float(momentum), C.c_uint32(optimizer),
+        _u64(keys), _f32(grads), C.c_uint64(len(keys)))
+    if rc == -1:
+        raise ValueError("key out of range")
     if rc != 0:
         raise RuntimeError(f"oracle strawman failed ({rc})")

@@ -389,6 +389,41 @@ int ecrm_oracle_update_rule(float *E, float *A, float *PE, float *PA,
     return 0;
 }
 
+/*
+ * Gradient propagation (the strawman of Sec. 3.3.1) under either update rule: every update is applied
+ * to its entry with the entry's state AND to the stripe's parity entry with the parity's state, in
+ * arrival order.  Adagrad's step depends on the state, so the parity drifts away from the sum of its
+ * entries.  The momentum rule breaks it too although it is linear: an update decays the parity's
+ * whole velocity, i.e. also the share of the stripe's entries that were not updated.  Both are
+ * pinned by hand-computed chains in the tests.
+ */
+int ecrm_oracle_update_gradient_propagation_rule(float *E, float *A, float *PE, float *PA,
+                                                 uint64_t R, uint32_t D, uint32_t k, float lr_f, float eps_f,
+                                                 float mu_f, uint32_t optimizer,
+                                                 const uint64_t *keys, const float *grads, uint64_t n)
+{
+    if (k == 0 || R % k != 0 || optimizer > 1) return -3;
+    for (uint64_t i = 0; i < n; ++i)
+        if (keys[i] >= R) return -1;
+    const double lr = (double)lr_f, eps = (double)eps_f, mu = (double)mu_f;
+    const uint64_t Gn = R / k;
+    double *E64 = widen(E, R * D), *A64 = widen(A, R * D);
+    double *PE64 = widen(PE, Gn * D), *PA64 = widen(PA, Gn * D);
+    if (!E64 || !A64 || !PE64 || !PA64) { free(E64); free(A64); free(PE64); free(PA64); return -2; }
+    for (uint64_t i = 0; i < n; ++i) {
+        const uint64_t x = keys[i], g = stripe_of(x, k);
+        for (uint32_t d = 0; d < D; ++d) {
+            const double gd = (double)grads[i * D + d];
+            rule_step(&E64[x * D + d], &A64[x * D + d], gd, optimizer, lr, eps, mu);
+            rule_step(&PE64[g * D + d], &PA64[g * D + d], gd, optimizer, lr, eps, mu);
+        }
+    }
+    narrow(E, E64, R * D);   narrow(A, A64, R * D);
+    narrow(PE, PE64, Gn * D); narrow(PA, PA64, Gn * D);
+    free(E64); free(A64); free(PE64); free(PA64);
+    return 0;
+}
+
 int ecrm_oracle_max_threads(void)
 {
 #ifdef _OPENMP

@@ -28,7 +28,7 @@ SYMBOLS = ["ecrm_create", "ecrm_destroy", "ecrm_data_bytes", "ecrm_parity_bytes"
 class EcrmConfig(C.Structure):
     _fields_ = [("rows", C.c_uint64), ("dim", C.c_uint32), ("k", C.c_uint32), ("servers", C.c_uint32),
                 ("optimizer", C.c_uint32), ("lr", C.c_float), ("eps", C.c_float), ("max_batch", C.c_uint64),
-                ("momentum", C.c_float), ("combine", C.c_uint32)]
+                ("momentum", C.c_float), ("combine", C.c_uint32), ("propagation", C.c_uint32)]
 
 
 class EcrmError(RuntimeError):
@@ -97,9 +97,9 @@ class Ecrm:
     """One context of the library.  Method names mirror the C entry points (ecrm_<name>)."""
 
     def __init__(self, rows, dim=128, k=4, servers=5, lr=0.01, eps=1e-8, max_batch=1 << 20, optimizer=0,
-                 momentum=0.0, combine=0):
+                 momentum=0.0, combine=0, propagation=0):
         self._lib = load_library()
-        self.cfg = EcrmConfig(rows, dim, k, servers, optimizer, lr, eps, max_batch, momentum, combine)
+        self.cfg = EcrmConfig(rows, dim, k, servers, optimizer, lr, eps, max_batch, momentum, combine, propagation)
         self._ctx = C.c_void_p(0)
         rc = self._lib.ecrm_create(C.byref(self.cfg), C.byref(self._ctx))
         if rc != ECRM_OK:

@@ -31,7 +31,7 @@ struct ecrm_ctx {
     uint32_t buf_cap, buf_cur;
     // profiling
     bool profiling;
-    hipEvent_t ev[ECRM_PROFILE_MAX_CALLS][ECRM_PHASES + 1];
+    hipEvent_t ev[ECRM_PROFILE_MAX_CALLS][2 * ECRM_PHASES + 1];   // a call with gradient propagation has the phases twice
     bool ev_made;
     uint32_t ev_calls;
 };
@@ -84,6 +84,8 @@ int ecrm_create(const ecrm_config *cfg, ecrm_ctx **out)
     if (cfg->servers < cfg->k + 1 || cfg->servers > 1024) return ECRM_EINVAL;
     if (cfg->optimizer != ECRM_OPT_ADAGRAD && cfg->optimizer != ECRM_OPT_MOMENTUM) return ECRM_EINVAL;
     if (cfg->combine > 1) return ECRM_EINVAL;
+    if (cfg->propagation > ECRM_PROP_NONE) return ECRM_EINVAL;
+    if (cfg->propagation == ECRM_PROP_GRADIENT && cfg->combine) return ECRM_EINVAL;
     if (!isfinite(cfg->lr) || !isfinite(cfg->eps) || cfg->eps < 0.0f) return ECRM_EINVAL;
     if (cfg->optimizer == ECRM_OPT_MOMENTUM && !(cfg->momentum >= 0.0f && cfg->momentum < 1.0f)) return ECRM_EINVAL;
     if (cfg->max_batch < 1 || cfg->max_batch > (1ull << 31)) return ECRM_EINVAL;
@@ -118,7 +120,7 @@ void ecrm_destroy(ecrm_ctx *c)
     if (!c) return;
     if (c->ev_made)
         for (int i = 0; i < ECRM_PROFILE_MAX_CALLS; ++i)
-            for (int j = 0; j <= ECRM_PHASES; ++j) (void)hipEventDestroy(c->ev[i][j]);
+            for (int j = 0; j <= 2 * ECRM_PHASES; ++j) (void)hipEventDestroy(c->ev[i][j]);
     delete c;
 }
 
@@ -218,16 +220,37 @@ static int run_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uin
     int key_bits = c->key_bits;
     if (c->rv.active)
         while (key_bits < 32 && (1ull << key_bits) <= c->cfg.rows) ++key_bits;
+    const uint32_t prop = c->cfg.propagation;
     uint32_t *sk = nullptr, *si = nullptr;
-    launch_sort(c->s, c->geo, c->rv, keys, n32, key_bits, &sk, &si, st);
+    launch_sort(c->s, c->geo, c->rv, keys, n32, key_bits, 1u, true, &sk, &si, st);
     if (c->rv.active)
         launch_hold_back(c->s, c->geo, c->rv, keys, grads, n32, c->buf_keys[target], c->buf_grads[target], c->buf_cap, st);
     if (ev) (void)hipEventRecord(ev[1], st);
     launch_chains(c->s, c->geo, c->A, grads, sk, si, n32, c->max_slots, c->max_pieces, c->cus, st);
     if (ev) (void)hipEventRecord(ev[2], st);
-    launch_apply(c->s, c->geo, c->E, c->A, c->PE, c->PA, c->load_data, c->load_parity, grads, sk, si, n32,
-                 c->cus, st);
-    if (ev) (void)hipEventRecord(ev[3], st);
+    const bool diff = prop == ECRM_PROP_DIFFERENCE;
+    launch_apply(c->s, c->geo, c->E, c->A, diff ? c->PE : nullptr, diff ? c->PA : nullptr, c->load_data,
+                 prop == ECRM_PROP_NONE ? nullptr : c->load_parity, grads, sk, si, n32, c->cus, st);
+    if (prop == ECRM_PROP_GRADIENT) {
+        // The strawman of Sec. 3.3.1: the parity server receives the gradient itself and applies the
+        // optimizer to the parity entry with the parity's own state.  The same pipeline once more,
+        // with the parity tables as the tables, grouped by stripe, every update of a stripe in
+        // arrival order.
+        Geometry gp = c->geo;
+        gp.k = 1;
+        int bits = 1;
+        while (bits < 32 && (1ull << bits) < c->cfg.rows / c->cfg.k) ++bits;
+        if (ev) (void)hipEventRecord(ev[3], st);
+        launch_reset(c->s, c->geo.S, n32, false, st);
+        launch_sort(c->s, c->geo, c->rv, keys, n32, bits, c->geo.k, false, &sk, &si, st);
+        if (ev) (void)hipEventRecord(ev[4], st);
+        launch_chains(c->s, gp, c->PA, grads, sk, si, n32, c->max_slots, c->max_pieces, c->cus, st);
+        if (ev) (void)hipEventRecord(ev[5], st);
+        launch_apply(c->s, gp, c->PE, c->PA, nullptr, nullptr, nullptr, nullptr, grads, sk, si, n32, c->cus, st);
+        if (ev) (void)hipEventRecord(ev[6], st);
+    } else if (ev) {
+        (void)hipEventRecord(ev[3], st);
+    }
     return check_launch();
 }
 
@@ -247,6 +270,7 @@ int ecrm_recovery_begin(ecrm_ctx *c, uint32_t server, uint32_t chunks, uint64_t 
     if (!c) return ECRM_EINVAL;
     if (!c->bound) return ECRM_ENOTBOUND;
     if (c->rv.active) return ECRM_ESTATE;
+    if (c->cfg.propagation != ECRM_PROP_DIFFERENCE) return ECRM_EINVAL;   // no parities a decoder could trust
     const uint32_t stripes = c->geo.rows / c->geo.k;
     if (server >= c->geo.S || chunks < 1 || chunks > stripes) return ECRM_EINVAL;
     if (capacity < 1 || capacity > c->max_batch || !aligned(buf_keys, 8) || !aligned(buf_grads, 16)) return ECRM_EINVAL;
@@ -398,7 +422,7 @@ int ecrm_profile(ecrm_ctx *c, int enable)
     if (!c) return ECRM_EINVAL;
     if (enable && !c->ev_made) {
         for (int i = 0; i < ECRM_PROFILE_MAX_CALLS; ++i)
-            for (int j = 0; j <= ECRM_PHASES; ++j)
+            for (int j = 0; j <= 2 * ECRM_PHASES; ++j)
                 if (hipEventCreate(&c->ev[i][j]) != hipSuccess) return ECRM_EHIP;
         c->ev_made = true;
     }
@@ -412,11 +436,12 @@ int ecrm_profile_read(ecrm_ctx *c, double *ms, uint64_t *calls)
     for (int j = 0; j < ECRM_PHASES; ++j) ms[j] = 0.0;
     *calls = c->ev_calls;
     for (uint32_t i = 0; i < c->ev_calls; ++i) {
-        if (hipEventSynchronize(c->ev[i][ECRM_PHASES]) != hipSuccess) return ECRM_EHIP;
-        for (int j = 0; j < ECRM_PHASES; ++j) {
+        const int sets = c->cfg.propagation == ECRM_PROP_GRADIENT ? 2 : 1;
+        if (hipEventSynchronize(c->ev[i][sets * ECRM_PHASES]) != hipSuccess) return ECRM_EHIP;
+        for (int j = 0; j < sets * ECRM_PHASES; ++j) {
             float t = 0.f;
             if (hipEventElapsedTime(&t, c->ev[i][j], c->ev[i][j + 1]) != hipSuccess) return ECRM_EHIP;
-            ms[j] += (double)t;
+            ms[j % ECRM_PHASES] += (double)t;
         }
     }
     c->ev_calls = 0;

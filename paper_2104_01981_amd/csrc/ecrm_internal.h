@@ -95,7 +95,8 @@ struct Geometry {
 // ---- launchers (each checks nothing: the API layer validates shapes before calling) -------------
 void launch_reset(const Scratch &s, uint32_t S, uint32_t n, bool clear_sticky, hipStream_t st);
 void launch_sort(const Scratch &s, const Geometry &g, const RecoveryView &rv, const uint64_t *keys, uint32_t n,
-                 int key_bits, uint32_t **sorted_keys, uint32_t **sorted_vals, hipStream_t st);
+                 int key_bits, uint32_t key_div, bool count_servers, uint32_t **sorted_keys,
+                 uint32_t **sorted_vals, hipStream_t st);
 void launch_hold_back(const Scratch &s, const Geometry &g, const RecoveryView &rv, const uint64_t *keys,
                       const float *grads, uint32_t n, unsigned long long *buf_keys, float *buf_grads,
                       uint32_t buf_cap, hipStream_t st);

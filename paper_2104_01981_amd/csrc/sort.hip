@@ -71,12 +71,26 @@ __global__ void set_buf_count_kernel(Header *h, uint32_t count)
     if (threadIdx.x == 0) h->buf_count = count;
 }
 
+// Sort key of one caller key in the first pass, the same in the histogram and in the scatter:
+// out-of-range keys keep their low bits (the batch is rejected anyway), held-back items get `rows`.
+__device__ __forceinline__ uint32_t first_pass_key(uint64_t k64, uint32_t rows, uint32_t k, uint32_t S_place,
+                                                   const RecoveryView &rv, uint32_t key_div, bool &bad, bool &held)
+{
+    const uint32_t key = (uint32_t)k64;
+    bad = k64 >= (uint64_t)rows;
+    held = !bad && held_back(rv, key, k, S_place);
+    if (held) return rows;
+    return key_div > 1u ? key / key_div : key;
+}
+
 // ---- histogram ---------------------------------------------------------------------------------
-// FIRST: keys are the caller's u64 row ids; also range check + load accounting.
+// FIRST: keys are the caller's u64 row ids; also range check + load accounting.  key_div > 1 groups by
+// row id / key_div instead (by stripe, for the parity half of gradient propagation).
 template <bool FIRST>
 __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
     const void *keys_in, uint32_t n, uint32_t nblocks, int shift, int bits, uint32_t *block_hist,
-    Header *hdr, unsigned long long *cnt, uint32_t rows, uint32_t k, uint32_t S, uint32_t S_place, RecoveryView rv)
+    Header *hdr, unsigned long long *cnt, uint32_t rows, uint32_t k, uint32_t S, uint32_t S_place, RecoveryView rv,
+    uint32_t key_div)
 {
     __shared__ uint32_t s_hist[kMaxBins];
     __shared__ uint32_t s_cnt[2 * 1024];
@@ -99,13 +113,11 @@ __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
             uint32_t key;
             if (FIRST) {
                 const uint64_t k64 = ((const uint64_t *)keys_in)[i];
-                key = (uint32_t)k64;
-                if (k64 >= (uint64_t)rows) {
-                    bad = true;
-                } else if (held_back(rv, key, k, S_place)) {
-                    key = rows;                                   // held back: sorts behind every row, not applied
-                } else if (S) {                                   // S == 0: the caller counts per distinct row later
-                    const uint32_t g = key / k, j = key - g * k;
+                bool oob, held;                                   // held back: sorts behind every row, not applied
+                key = first_pass_key(k64, rows, k, S_place, rv, key_div, oob, held);
+                bad |= oob;
+                if (!oob && !held && S) {                         // S == 0: the caller counts per distinct row later
+                    const uint32_t x = (uint32_t)k64, g = x / k, j = x - g * k;
                     atomicAdd(&s_cnt[(g + 1 + j) % S], 1u);       // server of the entry
                     atomicAdd(&s_cnt[S + g % S], 1u);             // server of its parity
                 }
@@ -154,7 +166,7 @@ template <bool FIRST>
 __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_kernel(
     const void *keys_in, const uint32_t *vals_in, uint32_t *keys_out, uint32_t *vals_out,
     const uint32_t *block_hist, const uint32_t *bin_total, uint32_t n, uint32_t nblocks, int shift, int bits,
-    uint32_t rows, uint32_t k, uint32_t S_place, RecoveryView rv)
+    uint32_t rows, uint32_t k, uint32_t S_place, RecoveryView rv, uint32_t key_div)
 {
     __shared__ uint32_t s_keys[kSortTile];
     __shared__ uint32_t s_vals[kSortTile];
@@ -177,9 +189,8 @@ __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_ke
         val[r] = 0;
         if (i < n) {
             if (FIRST) {
-                const uint64_t k64 = ((const uint64_t *)keys_in)[i];
-                key[r] = (uint32_t)k64;
-                if (k64 < (uint64_t)rows && held_back(rv, key[r], k, S_place)) key[r] = rows;
+                bool oob, held;
+                key[r] = first_pass_key(((const uint64_t *)keys_in)[i], rows, k, S_place, rv, key_div, oob, held);
                 val[r] = i;
             } else {
                 key[r] = ((const uint32_t *)keys_in)[i];
@@ -270,7 +281,8 @@ void launch_clear_status(const Scratch &s, hipStream_t st)
 }
 
 void launch_sort(const Scratch &s, const Geometry &g, const RecoveryView &rv, const uint64_t *keys, uint32_t n,
-                 int key_bits, uint32_t **sorted_keys, uint32_t **sorted_vals, hipStream_t st)
+                 int key_bits, uint32_t key_div, bool count_servers, uint32_t **sorted_keys,
+                 uint32_t **sorted_vals, hipStream_t st)
 {
     const uint32_t nblocks = (n + kSortTile - 1) / kSortTile;
     int passes = (key_bits + kMaxRadixBits - 1) / kMaxRadixBits;
@@ -285,22 +297,22 @@ void launch_sort(const Scratch &s, const Geometry &g, const RecoveryView &rv, co
         if (p == 0) {
             hipLaunchKernelGGL(sort_hist_kernel<true>, dim3(nblocks), dim3(kSortThreads), 0, st,
                                (const void *)keys, n, nblocks, shift, bits, s.block_hist, s.hdr, s.cnt,
-                               g.rows, g.k, (g.mode & 2u) ? 0u : g.S, g.S, rv);
+                               g.rows, g.k, (!count_servers || (g.mode & 2u)) ? 0u : g.S, g.S, rv, key_div);
             hipLaunchKernelGGL(sort_scan_kernel, dim3(bins), dim3(kSortThreads), 0, st, s.block_hist,
                                s.bin_total, nblocks);
             hipLaunchKernelGGL(sort_scatter_kernel<true>, dim3(nblocks), dim3(kSortThreads), 0, st,
                                (const void *)keys, (const uint32_t *)nullptr, s.keys[0], s.vals[0],
-                               s.block_hist, s.bin_total, n, nblocks, shift, bits, g.rows, g.k, g.S, rv);
+                               s.block_hist, s.bin_total, n, nblocks, shift, bits, g.rows, g.k, g.S, rv, key_div);
             cur = 0;
         } else {
             hipLaunchKernelGGL(sort_hist_kernel<false>, dim3(nblocks), dim3(kSortThreads), 0, st,
                                (const void *)s.keys[cur], n, nblocks, shift, bits, s.block_hist, s.hdr,
-                               s.cnt, g.rows, g.k, g.S, g.S, rv);
+                               s.cnt, g.rows, g.k, g.S, g.S, rv, 1u);
             hipLaunchKernelGGL(sort_scan_kernel, dim3(bins), dim3(kSortThreads), 0, st, s.block_hist,
                                s.bin_total, nblocks);
             hipLaunchKernelGGL(sort_scatter_kernel<false>, dim3(nblocks), dim3(kSortThreads), 0, st,
                                (const void *)s.keys[cur], s.vals[cur], s.keys[cur ^ 1], s.vals[cur ^ 1],
-                               s.block_hist, s.bin_total, n, nblocks, shift, bits, g.rows, g.k, g.S, rv);
+                               s.block_hist, s.bin_total, n, nblocks, shift, bits, g.rows, g.k, g.S, rv, 1u);
             cur ^= 1;
         }
         shift += bits;

@@ -513,7 +513,7 @@ struct ApplyArgs {
 // General path: the stripe whose first item sits at sorted position `pos` (wave-uniform), walked
 // through memory.  Used when the stripe does not fit the wave's window: runs of more than a few
 // dozen updates, and entries whose totals come from the split-chain path.
-template <int NC, int MODE>
+template <int NC, int MODE, bool PARITY>
 __device__ __forceinline__ void apply_stripe_general(const ApplyArgs &a, uint32_t n, uint32_t pos, uint32_t cb)
 {
     const uint32_t D = a.geo.D, k = a.geo.k;
@@ -526,8 +526,8 @@ __device__ __forceinline__ void apply_stripe_general(const ApplyArgs &a, uint32_
     D2 pe[NC], pa[NC];
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
-        pe[i] = widen2(ld2(perow, i));
-        pa[i] = widen2(ld2(parow, i));
+        pe[i] = PARITY ? widen2(ld2(perow, i)) : D2{0, 0};
+        pa[i] = PARITY ? widen2(ld2(parow, i)) : D2{0, 0};
     }
     uint32_t cur = pos;
     do {
@@ -605,10 +605,12 @@ __device__ __forceinline__ void apply_stripe_general(const ApplyArgs &a, uint32_
         key = cur < n ? uniform(a.sk[cur]) : kNoKey;
     } while (cur < n && key / k == g);
 
+    if (PARITY) {
 #pragma unroll
-    for (int i = 0; i < NC; ++i) {
-        st2(perow, i, narrow2(pe[i]));
-        st2(parow, i, narrow2(pa[i]));
+        for (int i = 0; i < NC; ++i) {
+            st2(perow, i, narrow2(pe[i]));
+            st2(parow, i, narrow2(pa[i]));
+        }
     }
 }
 
@@ -626,7 +628,7 @@ struct RowLoads {
     bool opens;
 };
 
-template <int NC>
+template <int NC, bool PARITY>
 __device__ __forceinline__ void issue_row(RowLoads<NC> &r, const ApplyArgs &a, uint32_t col0, uint32_t wkey,
                                           uint32_t widx, unsigned long long stripeheads, uint32_t j)
 {
@@ -644,7 +646,7 @@ __device__ __forceinline__ void issue_row(RowLoads<NC> &r, const ApplyArgs &a, u
         r.e[i] = ld2(erow, i);
         r.pe[i] = r.pa[i] = float2{0, 0};
     }
-    if (r.opens) {
+    if (PARITY && r.opens) {
         const uint32_t g = r.x / a.geo.k;
         const rsrc_t perow = row_f32(a.PE, g, D, col0), parow = row_f32(a.PA, g, D, col0);
 #pragma unroll
@@ -658,7 +660,7 @@ __device__ __forceinline__ void issue_row(RowLoads<NC> &r, const ApplyArgs &a, u
 // Window path: every stripe that opens in the first kChunk lanes of the wave's 64-position window
 // and ends inside the window.  Entries are taken one after the other; the loads of the next entry
 // are issued before the current one is computed, so two entries' rows are in flight per wave.
-template <int NC, int MODE>
+template <int NC, int MODE, bool PARITY>
 __device__ __forceinline__ void apply_window(const ApplyArgs &a, uint32_t wkey, uint32_t widx,
                                              unsigned long long rowheads, unsigned long long stripeheads,
                                              uint32_t first, uint32_t end, uint32_t cb)
@@ -673,7 +675,7 @@ __device__ __forceinline__ void apply_window(const ApplyArgs &a, uint32_t wkey, 
 #pragma unroll
     for (int s = 0; s < kPrefetch; ++s) {
         if (todo) {
-            issue_row<NC>(q[s], a, col0, wkey, widx, stripeheads, lowest_bit(todo));
+            issue_row<NC, PARITY>(q[s], a, col0, wkey, widx, stripeheads, lowest_bit(todo));
             todo &= todo - 1ull;
             qn = s + 1;
         }
@@ -687,7 +689,7 @@ __device__ __forceinline__ void apply_window(const ApplyArgs &a, uint32_t wkey, 
         for (int s = 0; s + 1 < kPrefetch; ++s) q[s] = q[s + 1];
         --qn;
         if (todo) {
-            issue_row<NC>(q[kPrefetch - 1], a, col0, wkey, widx, stripeheads, lowest_bit(todo));
+            issue_row<NC, PARITY>(q[kPrefetch - 1], a, col0, wkey, widx, stripeheads, lowest_bit(todo));
             todo &= todo - 1ull;
             ++qn;                                     // the queue was full before the pop: slot kPrefetch-1 is free
         }
@@ -738,7 +740,7 @@ __device__ __forceinline__ void apply_window(const ApplyArgs &a, uint32_t wkey, 
             pa[i].x += G[i].x - a64.x;
             pa[i].y += G[i].y - a64.y;
         }
-        if (!has_next || next_opens) {                // last entry of its stripe: the parity rows are complete
+        if (PARITY && (!has_next || next_opens)) {    // last entry of its stripe: the parity rows are complete
             const uint32_t g = cur.x / k;
             const rsrc_t perow = row_f32(a.PE, g, D, col0), parow = row_f32(a.PA, g, D, col0);
 #pragma unroll
@@ -751,7 +753,7 @@ __device__ __forceinline__ void apply_window(const ApplyArgs &a, uint32_t wkey, 
     }
 }
 
-template <int NC, int MODE>
+template <int NC, int MODE, bool PARITY>
 __device__ __forceinline__ void apply_stripes_body(const ApplyArgs &a)
 {
     if (a.hdr->batch_bad) return;
@@ -759,8 +761,8 @@ __device__ __forceinline__ void apply_stripes_body(const ApplyArgs &a)
     if (blockIdx.x == 0) {
         const uint32_t S = a.geo.S;
         for (uint32_t i = threadIdx.x; i < S; i += blockDim.x) {
-            a.load_data[i] += a.cnt[i];
-            a.load_parity[i] += a.cnt[S + i];
+            if (a.load_data) a.load_data[i] += a.cnt[i];
+            if (a.load_parity) a.load_parity[i] += a.cnt[S + i];
         }
     }
     const uint32_t n = min(a.n, a.hdr->n_valid), k = a.geo.k, lane = lane_id();
@@ -786,8 +788,8 @@ __device__ __forceinline__ void apply_stripes_body(const ApplyArgs &a)
         const bool last_inside = after != 0ull || p0 + kWave >= n;
         const uint32_t end = last_inside ? (after ? lowest_bit(after) : vend) : last;
         for (uint32_t cb = 0; cb < a.geo.ncb; ++cb) {
-            apply_window<NC, MODE>(a, wkey, widx, rowheads, stripeheads, first, end, cb);
-            if (!last_inside) apply_stripe_general<NC, MODE>(a, n, p0 + last, cb);
+            apply_window<NC, MODE, PARITY>(a, wkey, widx, rowheads, stripeheads, first, end, cb);
+            if (!last_inside) apply_stripe_general<NC, MODE, PARITY>(a, n, p0 + last, cb);
         }
     }
 }
@@ -796,12 +798,25 @@ __device__ __forceinline__ void apply_stripes_body(const ApplyArgs &a)
 template <int MODE>
 __global__ __launch_bounds__(256) void apply_stripes_kernel_d128(ApplyArgs a)
 {
-    apply_stripes_body<1, MODE>(a);
+    apply_stripes_body<1, MODE, true>(a);
 }
 template <int MODE>
 __global__ __launch_bounds__(256) void apply_stripes_kernel_d256(ApplyArgs a)
 {
-    apply_stripes_body<2, MODE>(a);
+    apply_stripes_body<2, MODE, true>(a);
+}
+// The same walk with the parity rows left alone: entries and their state only.  This is the update
+// of a system without redundancy (the baseline the overheads of Sec. 4.3 are quoted against), and
+// each of the two halves of the gradient-propagation strawman of Sec. 3.3.1.
+template <int MODE>
+__global__ __launch_bounds__(256) void apply_rows_kernel_d128(ApplyArgs a)
+{
+    apply_stripes_body<1, MODE, false>(a);
+}
+template <int MODE>
+__global__ __launch_bounds__(256) void apply_rows_kernel_d256(ApplyArgs a)
+{
+    apply_stripes_body<2, MODE, false>(a);
 }
 
 // Combined (synchronous) rule: one update per modified entry, so the per-server load counts one per
@@ -926,15 +941,25 @@ static void chains_for(const Scratch &s, const Geometry &g, const float *A, cons
 }
 
 template <int NC, int MODE>
-static void apply_for(const ApplyArgs &a, int cus, hipStream_t st)
+static void apply_for(const ApplyArgs &a, bool parity, int cus, hipStream_t st)
 {
-    static int grid_apply = 0;
-    if (NC == 1) {
-        if (!grid_apply) grid_apply = resident_grid(apply_stripes_kernel_d128<MODE>, cus);
-        hipLaunchKernelGGL(apply_stripes_kernel_d128<MODE>, dim3(grid_apply), dim3(256), 0, st, a);
+    static int grid_apply = 0, grid_rows = 0;
+    if (parity) {
+        if (NC == 1) {
+            if (!grid_apply) grid_apply = resident_grid(apply_stripes_kernel_d128<MODE>, cus);
+            hipLaunchKernelGGL(apply_stripes_kernel_d128<MODE>, dim3(grid_apply), dim3(256), 0, st, a);
+        } else {
+            if (!grid_apply) grid_apply = resident_grid(apply_stripes_kernel_d256<MODE>, cus);
+            hipLaunchKernelGGL(apply_stripes_kernel_d256<MODE>, dim3(grid_apply), dim3(256), 0, st, a);
+        }
     } else {
-        if (!grid_apply) grid_apply = resident_grid(apply_stripes_kernel_d256<MODE>, cus);
-        hipLaunchKernelGGL(apply_stripes_kernel_d256<MODE>, dim3(grid_apply), dim3(256), 0, st, a);
+        if (NC == 1) {
+            if (!grid_rows) grid_rows = resident_grid(apply_rows_kernel_d128<MODE>, cus);
+            hipLaunchKernelGGL(apply_rows_kernel_d128<MODE>, dim3(grid_rows), dim3(256), 0, st, a);
+        } else {
+            if (!grid_rows) grid_rows = resident_grid(apply_rows_kernel_d256<MODE>, cus);
+            hipLaunchKernelGGL(apply_rows_kernel_d256<MODE>, dim3(grid_rows), dim3(256), 0, st, a);
+        }
     }
 }
 
@@ -969,6 +994,7 @@ void launch_apply(const Scratch &s, const Geometry &g, float *E, float *A, float
                   unsigned long long *load_data, unsigned long long *load_parity, const float *grads,
                   const uint32_t *sk, const uint32_t *si, uint32_t n, int cus, hipStream_t st)
 {
+    const bool parity = PE != nullptr;      // no parity tables: entries and state only
     ApplyArgs a;
     a.E = E; a.A = A; a.PE = PE; a.PA = PA;
     a.grads = grads; a.sk = sk; a.si = si;
@@ -976,9 +1002,9 @@ void launch_apply(const Scratch &s, const Geometry &g, float *E, float *A, float
     a.hdr = s.hdr; a.cnt = s.cnt;
     a.load_data = load_data; a.load_parity = load_parity;
     a.n = n; a.geo = g;
-    if (g.mode == kAdagradCombine || g.mode == kMomentumCombine)      // one load count per modified entry
+    if ((g.mode == kAdagradCombine || g.mode == kMomentumCombine) && load_data)      // one load count per modified entry
         hipLaunchKernelGGL(count_rows_kernel, dim3(cus * 8), dim3(256), 0, st, sk, n, s.hdr, s.cnt, g.k, g.S);
-    ECRM_DISPATCH(apply_for, a, cus, st);
+    ECRM_DISPATCH(apply_for, a, parity, cus, st);
 }
 #undef ECRM_DISPATCH
 

@@ -20,7 +20,8 @@ def log(*a):
 
 class Case:
     def __init__(self, R, D, k, S, max_batch, seed=0, lr=si.DEFAULT_LR, eps=si.DEFAULT_EPS, optimizer=0,
-                 momentum=0.0, combine=0):
+                 momentum=0.0, combine=0, propagation=0):
+        self.propagation = propagation
         self.R, self.D, self.k, self.S, self.seed, self.lr, self.eps = R, D, k, S, seed, lr, eps
         self.optimizer, self.momentum, self.combine = optimizer, momentum, combine
         dev = "cuda:0"
@@ -30,7 +31,7 @@ class Case:
         self.PA = torch.zeros(R // k, D, device=dev)
         self.ld = torch.zeros(S, dtype=torch.int64, device=dev)
         self.lp = torch.zeros(S, dtype=torch.int64, device=dev)
-        self.ctx = Ecrm(R, D, k, S, lr, eps, max_batch, optimizer, momentum, combine)
+        self.ctx = Ecrm(R, D, k, S, lr, eps, max_batch, optimizer, momentum, combine, propagation)
         self.scratch = torch.empty(self.ctx.scratch_bytes(), dtype=torch.uint8, device=dev)
         self.ctx.bind(self.E, self.A, self.PE, self.PA, self.ld, self.lp, self.scratch)
         self.ctx.encode()
@@ -46,7 +47,17 @@ class Case:
         """keys_np: u64 host array; grads_t: [n, D] fp32 device tensor.  Runs both sides."""
         keys_t = torch.from_numpy(keys_np.view(np.int64)).to("cuda:0")
         self.ctx.update(keys_t, grads_t, n=len(keys_np))
-        if self.optimizer == 0 and self.combine == 0:
+        if self.propagation == 1:       # gradient propagation: the strawman, counted like the real thing
+            oracle.update_gradient_propagation_rule(self.hE, self.hA, self.hPE, self.hPA, self.k, self.lr, self.eps,
+                                                    keys_np, grads_t.cpu().numpy(), self.optimizer, self.momentum)
+            ld, lp = oracle.load(keys_np, self.R, self.k, self.S)
+            self.hld += ld
+            self.hlp += lp
+        elif self.propagation == 2:     # no redundancy: parities and their counters stay as they are
+            oracle.update_rule(self.hE, self.hA, self.hPE.copy(), self.hPA.copy(), self.k, self.S, self.lr, self.eps,
+                               self.momentum, self.optimizer, self.combine, keys_np, grads_t.cpu().numpy(),
+                               self.hld, np.zeros(self.S, np.uint64))
+        elif self.optimizer == 0 and self.combine == 0:
             oracle.update(self.hE, self.hA, self.hPE, self.hPA, self.k, self.S, self.lr, self.eps, keys_np,
                           grads_t.cpu().numpy(), self.hld, self.hlp, threads=min(16, oracle.max_threads()))
         else:

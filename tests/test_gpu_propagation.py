@@ -1,0 +1,90 @@
+"""GPU parity of the two other ways to treat the parities: the gradient-propagation strawman of
+Sec. 3.3.1 and no redundancy at all (the baseline of Sec. 4.3), against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from ecrm_case import Case, grads_for, log
+
+pytestmark = pytest.mark.gpu
+
+GRADIENT, NONE = 1, 2
+
+
+def _resid(c):
+    s = c.E.double().view(-1, c.k, c.D).sum(1)
+    return float((c.PE.double() - s).abs().max())
+
+
+@pytest.mark.parametrize("opt", [0, 1], ids=["adagrad", "momentum"])
+@pytest.mark.parametrize("R,D,k,S,n", [(4 * 2000, 128, 4, 5, 30011), (10 * 300, 256, 10, 11, 9000),
+                                       (3 * 700, 36, 3, 4, 5000), (4 * 64, 200, 4, 8, 70000), (2 * 500, 128, 2, 5, 1)])
+def test_gradient_propagation_shapes(opt, R, D, k, S, n):
+    c = Case(R, D, k, S, max_batch=n, seed=71, optimizer=opt, momentum=0.9, propagation=GRADIENT)
+    for call in range(2):
+        c.update(si.uniform_keys(71, call * n, n, R), grads_for(71, call * n, n, D))
+    log("gradient propagation", (opt, R, D, k, S, n), c.compare("gp"), "parity residual", _resid(c))
+    if n > 1000:
+        assert _resid(c) > 1e-4          # the strawman's parities are not the sums of their entries any more
+
+
+@pytest.mark.parametrize("opt", [0, 1], ids=["adagrad", "momentum"])
+@pytest.mark.parametrize("m", [257, 5000, 200000])
+def test_gradient_propagation_hot_stripe(opt, m):
+    # all updates fall on the k rows of one stripe: the parity's chain is the long one (split-chain path)
+    R, D, k, S = 1 << 10, 128, 4, 5
+    c = Case(R, D, k, S, max_batch=m, seed=73, optimizer=opt, momentum=0.9, propagation=GRADIENT)
+    keys = (np.uint64(320) + (si.uniform_keys(73, 0, m, 1 << 20) % np.uint64(k))).astype(np.uint64)
+    c.update(keys, grads_for(73, 0, m, D))
+    log("hot stripe", (opt, m), c.ctx.batch_stats(), c.compare(f"gp-hot{m}"))
+
+
+def test_gradient_propagation_skewed_workload():
+    w = si.WORKLOADS["hbm_scale"]
+    shift = 8
+    R, per = w["R"] >> shift, (w["n"] >> shift) // w["batches"]
+    c = Case(R, si.DEFAULT_D, si.DEFAULT_K, si.DEFAULT_S, per, seed=w["seed"], propagation=GRADIENT)
+    for b in range(2):
+        c.update(si.workload_keys("hbm_scale", batch=b, scale_shift=shift), grads_for(w["seed"], b * per, per, si.DEFAULT_D))
+    log("skewed", c.compare("gp-skewed"), "parity residual", _resid(c))
+
+
+def test_gradient_propagation_rejects_bad_batch_whole():
+    R, D, k, S, n = 4 * 500, 128, 4, 5, 3000
+    c = Case(R, D, k, S, max_batch=n, seed=75, propagation=GRADIENT)
+    before = [t.clone() for t in (c.E, c.A, c.PE, c.PA, c.ld, c.lp)]
+    keys = si.uniform_keys(75, 0, n, R)
+    keys[n // 2] = R
+    c.ctx.update(torch.from_numpy(keys.view(np.int64)).cuda(), grads_for(75, 0, n, D), n=n)
+    assert c.ctx.status() != 0
+    for a, b in zip(before, (c.E, c.A, c.PE, c.PA, c.ld, c.lp)):
+        assert torch.equal(a, b)
+    c.ctx.clear_status()
+    c.update(si.uniform_keys(75, n, n, R), grads_for(75, n, n, D))
+    c.compare("gp after rejected batch")
+
+
+@pytest.mark.parametrize("opt,comb", [(0, 0), (1, 0), (0, 1), (1, 1)],
+                         ids=["adagrad", "momentum", "adagrad-combined", "momentum-combined"])
+@pytest.mark.parametrize("R,D,k,S,n", [(4 * 2000, 128, 4, 5, 30011), (10 * 300, 256, 10, 11, 9000), (4 * 64, 200, 4, 8, 70000)])
+def test_no_redundancy(opt, comb, R, D, k, S, n):
+    c = Case(R, D, k, S, max_batch=n, seed=79, optimizer=opt, momentum=0.9, combine=comb, propagation=NONE)
+    pe0, pa0 = c.PE.clone(), c.PA.clone()
+    for call in range(2):
+        c.update(si.uniform_keys(79, call * n, n, R), grads_for(79, call * n, n, D))
+    log("no redundancy", (opt, comb, R, D, k, S, n), c.compare("none"))
+    assert torch.equal(pe0, c.PE) and torch.equal(pa0, c.PA)          # bit for bit untouched
+    assert int(c.lp.sum()) == 0
+
+
+def test_propagation_config_errors():
+    from paper_2104_01981_amd import Ecrm, EcrmError
+    for kw in (dict(propagation=3), dict(propagation=GRADIENT, combine=1)):
+        with pytest.raises(EcrmError):
+            Ecrm(4 * 100, 128, 4, 5, 0.01, 1e-8, 100, **kw)
+    c = Case(4 * 100, 128, 4, 5, max_batch=100, propagation=NONE)
+    buf_k = torch.empty(200, dtype=torch.int64, device="cuda:0")
+    buf_g = torch.empty(200, 128, device="cuda:0")
+    with pytest.raises(EcrmError):
+        c.ctx.recovery_begin(0, 1, buf_k, buf_g, 100)
