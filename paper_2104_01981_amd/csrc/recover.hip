@@ -62,17 +62,20 @@ __device__ __forceinline__ void rebuild_row(float *T, float *P, uint32_t g, int 
             x = (double)p.x;
             y = (double)p.y;
         }
-        for (uint32_t j0 = 0; j0 < k; j0 += 4) {             // four member rows in flight
+        // the surviving members only (the lost row is never read): m-th survivor is member m, or m+1 past the lost one
+        const uint32_t nsrc = lost == (int)k ? k : k - 1u;
+        for (uint32_t m0 = 0; m0 < nsrc; m0 += 4) {          // four member rows in flight
             float2 v[4];
 #pragma unroll
             for (uint32_t u = 0; u < 4; ++u) {
-                const uint32_t j = min(j0 + u, k - 1);
-                v[u] = ldr(row_of(T, (size_t)g * k + j, D), s);
+                const uint32_t m = m0 + u;
+                const uint32_t j = (int)m < lost ? m : m + 1u;
+                v[u] = float2{0.f, 0.f};
+                if (m < nsrc) v[u] = ldr(row_of(T, (size_t)g * k + j, D), s);
             }
 #pragma unroll
             for (uint32_t u = 0; u < 4; ++u) {
-                const uint32_t j = j0 + u;
-                if (j < k && (int)j != lost) {
+                if (m0 + u < nsrc) {
                     if (lost == (int)k) { x += (double)v[u].x; y += (double)v[u].y; }
                     else { x -= (double)v[u].x; y -= (double)v[u].y; }
                 }
