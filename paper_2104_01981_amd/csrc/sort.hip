@@ -71,6 +71,23 @@ __global__ void set_buf_count_kernel(Header *h, uint32_t count)
     if (threadIdx.x == 0) h->buf_count = count;
 }
 
+// Tile a block works on.  Workgroups go to the 8 XCDs (each with its own L2) round-robin by block id;
+// with this map every XCD gets a contiguous range of tiles, so the short runs that neighbouring
+// tiles write next to each other in a digit's output range meet in one L2 instead of in memory.
+#ifndef ECRM_XCD_TILES
+#define ECRM_XCD_TILES 1
+#endif
+__device__ __forceinline__ uint32_t tile_of_block(uint32_t b, uint32_t nblocks)
+{
+#if ECRM_XCD_TILES
+    constexpr uint32_t X = 8;
+    const uint32_t q = nblocks / X, r = nblocks % X, xcd = b % X, i = b / X;
+    return xcd < r ? xcd * (q + 1u) + i : r * (q + 1u) + (xcd - r) * q + i;
+#else
+    return b;
+#endif
+}
+
 // Sort key of one caller key in the first pass, the same in the histogram and in the scatter:
 // out-of-range keys keep their low bits (the batch is rejected anyway), held-back items get `rows`.
 __device__ __forceinline__ uint32_t first_pass_key(uint64_t k64, uint32_t rows, uint32_t k, uint32_t S_place,
@@ -103,7 +120,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
         if (tid == 0) s_bad = 0;
     }
     __syncthreads();
-    const uint32_t tile0 = blockIdx.x * (uint32_t)kSortTile;
+    const uint32_t tile = tile_of_block(blockIdx.x, nblocks), tile0 = tile * (uint32_t)kSortTile;
     const uint32_t wave = tid / kWave, lane = lane_id();
     bool bad = false;
 #pragma unroll 4
@@ -129,7 +146,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
     }
     if (FIRST && bad) s_bad = 1;
     __syncthreads();
-    for (uint32_t b = tid; b < bins; b += kSortThreads) block_hist[(size_t)b * nblocks + blockIdx.x] = s_hist[b];
+    for (uint32_t b = tid; b < bins; b += kSortThreads) block_hist[(size_t)b * nblocks + tile] = s_hist[b];
     if (FIRST) {
         for (uint32_t i = tid; i < 2 * S; i += kSortThreads)
             if (s_cnt[i]) atomicAdd(&cnt[i], (unsigned long long)s_cnt[i]);
@@ -180,7 +197,7 @@ __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_ke
     for (uint32_t i = tid; i < kSortWaves * kMaxBins; i += kSortThreads) (&s_wcnt[0][0])[i] = 0;
     __syncthreads();
 
-    const uint32_t tile0 = blockIdx.x * (uint32_t)kSortTile;
+    const uint32_t tile = tile_of_block(blockIdx.x, nblocks), tile0 = tile * (uint32_t)kSortTile;
     uint32_t key[kSortIpt], val[kSortIpt], rank[kSortIpt];
 #pragma unroll
     for (int r = 0; r < kSortIpt; ++r) {
@@ -239,7 +256,7 @@ __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_ke
     const uint32_t gstart = block_excl_scan(gtot, s_wave, dummy);
     if (tid < bins) {
         s_binstart[tid] = binstart;
-        s_gbase[tid] = gstart + block_hist[(size_t)tid * nblocks + blockIdx.x] - binstart;
+        s_gbase[tid] = gstart + block_hist[(size_t)tid * nblocks + tile] - binstart;
     }
     __syncthreads();
 
