@@ -76,7 +76,7 @@ def main():
     ap.add_argument("--fresh-process-retry", type=int, default=1,
                     help="if every arena of this process probes slow, release the memory and run the benchmark "
                          "once more in a child process (0 disables)")
-    ap.add_argument("--placement-accept-frac", type=float, default=0.67,
+    ap.add_argument("--placement-accept-frac", type=float, default=0.70,
                     help="the probe accepts an arena when the apply kernel reaches this fraction of the HBM peak")
     ap.add_argument("--order", default="E,g0,g1,A,g2,g3,PE,PA,scratch,keys,g*",
                     help="arena only: order of the resident arrays (gN = batch N, padN = N GiB of padding)")

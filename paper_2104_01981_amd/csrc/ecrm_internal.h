@@ -40,7 +40,8 @@ struct Header {
                            // carry the row id `rows` and sort behind them
     uint32_t n_held;       // items of the batch held back
     uint32_t buf_count;    // held-back items waiting in the buffer (all batches)
-    uint32_t pad[55];
+    uint32_t apply_ticket; // next group of sorted positions the apply kernel hands out (cleared by reset)
+    uint32_t pad[54];
 };
 static_assert(sizeof(Header) == 256, "header is one 256-byte block");
 

@@ -53,6 +53,7 @@ __global__ void reset_kernel(Header *h, unsigned long long *cnt, uint32_t S, uin
         h->n_long_items = 0;
         h->n_valid = n;
         h->n_held = 0;
+        h->apply_ticket = 0;
         if (clear_sticky) {
             h->err_sticky = 0;
             h->buf_count = 0;
