@@ -71,15 +71,17 @@ def main():
     ap.add_argument("--no-recovery", action="store_true", help="skip the recovery-decode measurement")
     ap.add_argument("--layout", default="arena", choices=["arena", "separate"],
                     help="one arena in --order, or one torch allocation per array")
-    ap.add_argument("--placement-trials", type=int, default=2,
+    ap.add_argument("--placement-trials", type=int, default=3,
                     help="how many arenas to try at most when the placement probe is slow")
     ap.add_argument("--fresh-process-retry", type=int, default=1,
                     help="if every arena of this process probes slow, release the memory and run the benchmark "
                          "once more in a child process (0 disables)")
     ap.add_argument("--placement-accept-frac", type=float, default=0.70,
                     help="the probe accepts an arena when the apply kernel reaches this fraction of the HBM peak")
-    ap.add_argument("--order", default="E,g0,g1,A,g2,g3,PE,PA,scratch,keys,g*",
-                    help="arena only: order of the resident arrays (gN = batch N, padN = N GiB of padding)")
+    ap.add_argument("--order", default="",
+                    help="arena only: order of the resident arrays (gN = batch N, padN = N GiB of padding); "
+                         "default: the built-in list of geometries, one per placement trial")
+    ap.add_argument("--first-geometry", type=int, default=0, help="index of the geometry the first trial uses")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain device-to-device copies of 8 GiB (to scale rocprof's HBM byte counters)")
     ap.add_argument("--per-step", action="store_true",
@@ -142,26 +144,38 @@ def main():
     for b in range(nb):
         sizes[f"keys{b}"] = per * 8
         sizes[f"grads{b}"] = per * D * 4
-    order, npad = [], 0
-    for tok in args.order.split(","):
-        if tok == "g*":
-            order += [f"grads{b}" for b in range(nb) if f"grads{b}" not in order]
-        elif tok == "keys":
-            order += [f"keys{b}" for b in range(nb)]
-        elif tok.startswith("pad"):
-            sizes[f"_pad{npad}"] = int(float(tok[3:]) * (1 << 30))
-            order.append(f"_pad{npad}")
-            npad += 1
-        elif tok.startswith("g"):
-            if int(tok[1:]) < nb:
-                order.append(f"grads{int(tok[1:])}")
-        elif tok:
-            order.append(tok)
-    order += [n_ for n_ in sizes if n_ not in order]
-    offs, total = {}, 0
-    for name in order:
-        offs[name] = total
-        total += (sizes[name] + ALIGN - 1) // ALIGN * ALIGN
+    # Geometries tried one after the other while the placement probe stays slow.  All keep the tables
+    # that are swept together >= 32 GiB apart; they differ in what lies between them, so that the
+    # driver's (deterministic) physical placement differs too.
+    GEOMETRIES = ["E,g0,g1,A,g2,g3,PE,PA,scratch,keys,g*",
+                  "E,g0,g1,g2,A,g3,g4,g5,PE,g6,PA,scratch,keys,g*",
+                  "g0,E,g1,g2,A,g3,g4,PE,g5,PA,scratch,keys,g*",
+                  "E,g0,g1,pad8,A,g2,g3,pad8,PE,g4,PA,scratch,keys,g*",
+                  "separate"]
+
+    def geometry(spec):
+        """offsets of the resident arrays inside one arena, and its size"""
+        sz, order, npad = dict(sizes), [], 0
+        for tok in spec.split(","):
+            if tok == "g*":
+                order += [f"grads{b}" for b in range(nb) if f"grads{b}" not in order]
+            elif tok == "keys":
+                order += [f"keys{b}" for b in range(nb)]
+            elif tok.startswith("pad"):
+                sz[f"_pad{npad}"] = int(float(tok[3:]) * (1 << 30))
+                order.append(f"_pad{npad}")
+                npad += 1
+            elif tok.startswith("g"):
+                if int(tok[1:]) < nb:
+                    order.append(f"grads{int(tok[1:])}")
+            elif tok:
+                order.append(tok)
+        order += [n_ for n_ in sz if n_ not in order]
+        offs, total = {}, 0
+        for name in order:
+            offs[name] = total
+            total += (sz[name] + ALIGN - 1) // ALIGN * ALIGN
+        return offs, total
     CH = 1 << 22                                  # rows generated per slice (2 GiB of fp32 at D = 128)
 
     def fill_tables():
@@ -198,15 +212,19 @@ def main():
     # Physical placement is the driver's; now and then (e.g. right after another process released a
     # lot of memory) the same virtual layout lands badly and every kernel that sweeps the tables runs
     # ~15 % slower for the life of the allocation.  Probe with three updates of batch 0 and, if the
-    # apply kernel is clearly off its usual rate, release the arena and take a new one.
-    placement = []
+    # apply kernel is clearly off its usual rate, release the memory and take the next geometry.
+    placement, geometries = [], []
     for trial in range(max(1, args.placement_trials)):
-        if args.layout == "separate":
-            pieces = {name: torch.empty(sizes[name], dtype=torch.uint8, device=dev) for name in order}
+        spec = args.order or GEOMETRIES[(args.first_geometry + trial) % len(GEOMETRIES)]
+        separate = args.layout == "separate" or spec == "separate"
+        geometries.append("separate" if separate else spec)
+        if separate:
+            pieces = {name: torch.empty(sizes[name], dtype=torch.uint8, device=dev) for name in sizes}
 
             def carve(name, dtype, shape):
                 return pieces[name].view(dtype).view(shape)
         else:
+            offs, total = geometry(spec)
             arena = torch.empty(total, dtype=torch.uint8, device=dev)
 
             def carve(name, dtype, shape):
@@ -233,31 +251,31 @@ def main():
         placement.append(round(probe_frac, 4))
         if trial + 1 >= args.placement_trials or probe_frac >= args.placement_accept_frac:
             break
-        log(f"placement trial {trial}: apply kernel at {probe_frac:.3f} of the HBM peak, taking another arena")
-        blocker = torch.empty(8 << 30, dtype=torch.uint8, device=dev)     # keeps the next arena off the same pages
+        log(f"placement trial {trial} ({geometries[-1]}): apply kernel at {probe_frac:.3f} of the HBM peak, "
+            "trying the next geometry")
         ctx.drop_buffers()
         del E, A, PE, PA, ld, lp, scratch, keys, grads
-        if args.layout == "separate":
+        if separate:
             del pieces
         else:
             del arena
         torch.cuda.synchronize()
         torch.cuda.empty_cache()
-        del blocker
     if placement[-1] < args.placement_accept_frac and args.fresh_process_retry > 0:
         # every arena this process obtained is slow: hand over to a child process with fresh mappings
         import subprocess
-        log(f"placement: {len(placement)} arenas at {placement} of the HBM peak; retrying in a fresh process")
+        log(f"placement: {len(placement)} geometries at {placement} of the HBM peak; retrying in a fresh process")
         ctx.drop_buffers()
         del E, A, PE, PA, ld, lp, scratch, keys, grads
-        if args.layout == "separate":
+        if separate:
             del pieces
         else:
             del arena
         torch.cuda.synchronize()
         torch.cuda.empty_cache()
         argv = [a for a in sys.argv[1:]]
-        rc = subprocess.call([sys.executable, os.path.abspath(__file__), *argv, "--fresh-process-retry", "0"],
+        rc = subprocess.call([sys.executable, os.path.abspath(__file__), *argv, "--fresh-process-retry", "0",
+                              "--first-geometry", str(args.first_geometry + len(placement))],
                              env=dict(os.environ, ECRM_BENCH_PARENT_PROBES=json.dumps(placement)))
         sys.exit(rc)
     fill_tables()                                  # the probe's updates are undone: tables start from the recipe
@@ -345,7 +363,7 @@ def main():
                      "traffic": measured_traffic(args.workload, sh, variant),
                      "algorithmic_bytes_per_launch": apply_bytes, "avg_launch_ms": apply_ms},
         "phases_ms_per_step": {"group": ms[0] / calls, "chains": ms[1] / calls, "apply": apply_ms},
-        "placement": {"arenas_tried": len(placement), "probe_apply_frac": placement,
+        "placement": {"arenas_tried": len(placement), "probe_apply_frac": placement, "geometry": geometries[-1],
                       "parent_process_probes": json.loads(os.environ.get("ECRM_BENCH_PARENT_PROBES", "null"))},
         "path": {"algorithmic_bytes_per_step": path_bytes, "achieved_GBps": path_gbs,
                  "frac_of_hbm_peak": path_gbs / HBM_PEAK_GBS},
@@ -398,39 +416,38 @@ def main():
 
         # training while server 0 is rebuilt chunk by chunk: the decoder on a second stream, one update
         # batch enqueued while each chunk is locked, buffered updates replayed at every unlock
-        if args.layout == "arena":
-            buf_keys = torch.empty(2 * per, dtype=torch.int64, device=dev)
-            buf_grads = torch.empty(2 * per, D, device=dev)
-            side, main = torch.cuda.Stream(), torch.cuda.current_stream()
-            under_load = {}
-            for chunks in (1, 10):
-                ctx.recovery_begin(0, chunks, buf_keys, buf_grads, per)
-                torch.cuda.synchronize()
-                tr0 = time.perf_counter()
-                waiting = 0
-                for ch in range(chunks):
-                    ctx.recovery_lock()
-                    ev, done = torch.cuda.Event(), torch.cuda.Event()
-                    ev.record(main)
-                    side.wait_event(ev)
-                    ctx.recovery_decode(stream=side)
-                    done.record(side)
-                    ctx.update(keys[ch % nb], grads[ch % nb])
-                    main.wait_event(done)
-                    waiting = max(waiting, ctx.recovery_state()["buffered"])
-                    ctx.recovery_unlock()
-                torch.cuda.synchronize()
-                tr1 = time.perf_counter()
-                rc_status = ctx.status()
-                under_load[str(chunks)] = {
-                    "recovery_ms": (tr1 - tr0) * 1e3, "updates_applied_meanwhile": chunks * per,
-                    "items_per_s_during_recovery": chunks * per / (tr1 - tr0),
-                    "relative_to_normal": chunks * per / (tr1 - tr0) / value,
-                    "max_updates_waiting": waiting, "status": rc_status}
-                if rc_status != 0:
-                    ctx.clear_status()
-            out["recovery"]["under_load"] = under_load
-            del buf_keys, buf_grads
+        buf_keys = torch.empty(2 * per, dtype=torch.int64, device=dev)
+        buf_grads = torch.empty(2 * per, D, device=dev)
+        side, main = torch.cuda.Stream(), torch.cuda.current_stream()
+        under_load = {}
+        for chunks in (1, 10):
+            ctx.recovery_begin(0, chunks, buf_keys, buf_grads, per)
+            torch.cuda.synchronize()
+            tr0 = time.perf_counter()
+            waiting = 0
+            for ch in range(chunks):
+                ctx.recovery_lock()
+                ev, done = torch.cuda.Event(), torch.cuda.Event()
+                ev.record(main)
+                side.wait_event(ev)
+                ctx.recovery_decode(stream=side)
+                done.record(side)
+                ctx.update(keys[ch % nb], grads[ch % nb])
+                main.wait_event(done)
+                waiting = max(waiting, ctx.recovery_state()["buffered"])
+                ctx.recovery_unlock()
+            torch.cuda.synchronize()
+            tr1 = time.perf_counter()
+            rc_status = ctx.status()
+            under_load[str(chunks)] = {
+                "recovery_ms": (tr1 - tr0) * 1e3, "updates_applied_meanwhile": chunks * per,
+                "items_per_s_during_recovery": chunks * per / (tr1 - tr0),
+                "relative_to_normal": chunks * per / (tr1 - tr0) / value,
+                "max_updates_waiting": waiting, "status": rc_status}
+            if rc_status != 0:
+                ctx.clear_status()
+        out["recovery"]["under_load"] = under_load
+        del buf_keys, buf_grads
 
     if not args.no_cpu_baseline:
         import oracle

@@ -775,13 +775,19 @@ __device__ __forceinline__ void apply_stripes_body(const ApplyArgs &a)
 #define ECRM_APPLY_DYNAMIC 8
 #endif
 #if ECRM_APPLY_DYNAMIC
-    uint32_t ch = 0, left = 0;
+    // a wave's first ticket is its own number (no counter traffic at start-up, which is all a small
+    // batch consists of); later ones come from the counter.  Small batches get smaller tickets, so
+    // that every wave has work.
+    const uint32_t per_ticket = min((uint32_t)ECRM_APPLY_DYNAMIC, max(1u, nchunks / (4u * wave_count())));
+    uint32_t ch = wave_id() * per_ticket, left = per_ticket;
     for (;; ++ch) {
         if (left == 0) {
+            // every ticket was a first ticket: nothing to fetch (and no counter traffic for small batches)
+            if ((nchunks + per_ticket - 1) / per_ticket <= wave_count()) break;
             uint32_t t = 0;
             if (lane == 0) t = atomicAdd(&a.hdr->apply_ticket, 1u);
-            ch = uniform(t) * (uint32_t)ECRM_APPLY_DYNAMIC;
-            left = ECRM_APPLY_DYNAMIC;
+            ch = (wave_count() + uniform(t)) * per_ticket;
+            left = per_ticket;
         }
         --left;
         if (ch >= nchunks) break;
