@@ -76,8 +76,10 @@ def main():
     ap.add_argument("--fresh-process-retry", type=int, default=1,
                     help="if every arena of this process probes slow, release the memory and run the benchmark "
                          "once more in a child process (0 disables)")
-    ap.add_argument("--placement-accept-frac", type=float, default=0.70,
-                    help="the probe accepts an arena when the apply kernel reaches this fraction of the HBM peak")
+    ap.add_argument("--placement-accept-frac", type=float, default=None,
+                    help="the probe accepts an arena when the apply kernel reaches this fraction of the HBM peak "
+                         "(default: 0.70 for the default workload and configuration, whose usual rate is known; "
+                         "0 = accept the first arena for every other one)")
     ap.add_argument("--order", default="",
                     help="arena only: order of the resident arrays (gN = batch N, padN = N GiB of padding); "
                          "default: the built-in list of geometries, one per placement trial")
@@ -131,6 +133,8 @@ def main():
     if args.propagation != "difference":
         variant += f"/{args.propagation}-propagation"
     prop = {"difference": 0, "gradient": 1, "none": 2}[args.propagation]
+    if args.placement_accept_frac is None:
+        args.placement_accept_frac = 0.70 if (args.workload == "hbm_scale" and not sh and not variant) else 0.0
 
     t_setup = time.perf_counter()
     ctx = Ecrm(R, D, k, S, si.DEFAULT_LR, si.DEFAULT_EPS, per, optimizer=1 if args.optimizer == "momentum" else 0,
