@@ -26,9 +26,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the apply kernel on the default workload, from rocprofv3 FETCH_SIZE and
 # WRITE_SIZE scaled by a plain copy of known size (profiles/update_path_hbm_scale_hbm_traffic.txt).
 # Reported only while the kernel's sources are the ones the counters were taken on.
-TRAFFIC_BYTES_PER_LAUNCH = 37781674980
+TRAFFIC_BYTES_PER_LAUNCH = 37657541413
 TRAFFIC_SOURCES = ["paper_2104_01981_amd/csrc/update.hip", "paper_2104_01981_amd/csrc/ecrm_internal.h"]
-TRAFFIC_SOURCES_SHA256 = "5a911ede1834d483a4ecf96cfa1464e35fa6004a7b2dd5e51590000b792a569b"
+TRAFFIC_SOURCES_SHA256 = "50793aa5672ca247e39fb8f3f602cf8d0719da5a8ff1f61726cefb64fa4da006"
 
 
 def measured_traffic(workload, scale_shift, variant=""):
