@@ -23,6 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+LONG_RUN = 1024          # ECRM_LONG_RUN of include/ecrm.h: longer runs leave the apply kernel for the split-chain path
 # HBM bytes per launch of the apply kernel on the default workload, from rocprofv3 FETCH_SIZE and
 # WRITE_SIZE scaled by a plain copy of known size (profiles/update_path_hbm_scale_hbm_traffic.txt).
 # Reported only while the kernel's sources are the ones the counters were taken on.
@@ -203,12 +204,12 @@ def main():
         uk, cnt = torch.unique(kt, return_counts=True)
         U = int(uk.numel())
         Up = int(torch.unique(uk // k).numel())
-        n_long = int(cnt[cnt > 256].sum())
+        n_long = int(cnt[cnt > LONG_RUN].sum())
         if prop == 2:        # no parities
             return per * (8 + 4 * D) + U * 16 * D, per * 8 + (per - n_long) * 4 * D + U * 16 * D
         if prop == 1:        # every gradient goes to two servers; the two apply launches together
             _, pcnt = torch.unique(kt // k, return_counts=True)
-            n_long_p = int(pcnt[pcnt > 256].sum())
+            n_long_p = int(pcnt[pcnt > LONG_RUN].sum())
             return (2 * per * (8 + 4 * D) + (U + Up) * 16 * D,
                     2 * per * 8 + (2 * per - n_long - n_long_p) * 4 * D + (U + Up) * 16 * D)
         return per * (8 + 4 * D) + (U + Up) * 16 * D, per * 8 + (per - n_long) * 4 * D + (U + Up) * 16 * D
@@ -367,6 +368,9 @@ def main():
                      "traffic": measured_traffic(args.workload, sh, variant),
                      "algorithmic_bytes_per_launch": apply_bytes, "avg_launch_ms": apply_ms},
         "phases_ms_per_step": {"group": ms[0] / calls, "chains": ms[1] / calls, "apply": apply_ms},
+        "device": {"name": torch.cuda.get_device_properties(0).name,
+                   "uuid": str(getattr(torch.cuda.get_device_properties(0), "uuid", "")),
+                   "compute_units": torch.cuda.get_device_properties(0).multi_processor_count},
         "placement": {"arenas_tried": len(placement), "probe_apply_frac": placement, "geometry": geometries[-1],
                       "parent_process_probes": json.loads(os.environ.get("ECRM_BENCH_PARENT_PROBES", "null"))},
         "path": {"algorithmic_bytes_per_step": path_bytes, "achieved_GBps": path_gbs,

@@ -194,7 +194,7 @@ int ecrm_clear_status(ecrm_ctx *ctx, void *hip_stream);
  *   out[1] = chain pieces those were cut into,  out[2] = items in those entries,
  *   out[3] = 1 if the batch was rejected for a bad key. */
 enum { ECRM_PHASE_GROUP = 0, ECRM_PHASE_CHAINS = 1, ECRM_PHASE_APPLY = 2, ECRM_PHASES = 3 };
-enum { ECRM_PROFILE_MAX_CALLS = 256, ECRM_LONG_RUN = 256 };
+enum { ECRM_PROFILE_MAX_CALLS = 256, ECRM_LONG_RUN = 1024 };
 int ecrm_profile(ecrm_ctx *ctx, int enable);
 int ecrm_profile_read(ecrm_ctx *ctx, double *ms, uint64_t *calls);
 int ecrm_batch_stats(ecrm_ctx *ctx, void *hip_stream, uint64_t *out);

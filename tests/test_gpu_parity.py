@@ -11,6 +11,8 @@ from ecrm_case import Case, grads_for, log
 
 pytestmark = pytest.mark.gpu
 
+LONG_RUN = 1024      # ECRM_LONG_RUN of include/ecrm.h
+
 
 def test_generator_matches_on_device():
     a = si.grads(5, 1000, 4096, 128, "cuda:0").cpu()
@@ -75,17 +77,17 @@ def test_shapes(R, D, k, S, n):
     c.check_invariant()
 
 
-@pytest.mark.parametrize("m", [1, 2, 255, 256, 257, 258, 5000, 300000])
+@pytest.mark.parametrize("m", [1, 2, 255, 256, 257, 1023, 1024, 1025, 1026, 5000, 300000])
 def test_one_hot_row(m):
     """All updates on one entry: the run goes through the split-chain path once it is longer than
-    256 (the two lengths around the threshold take different paths and must agree with the oracle)."""
+    1024 (the two lengths around the threshold take different paths and must agree with the oracle)."""
     R, D, k, S = 1 << 10, 128, 4, 5
     c = Case(R, D, k, S, max_batch=m, seed=23)
     keys = np.full(m, 777, np.uint64)
     c.update(keys, grads_for(23, 0, m, D))
     stats = c.ctx.batch_stats()
-    assert stats["long_rows"] == (1 if m > 256 else 0)
-    assert stats["long_items"] == (m if m > 256 else 0)
+    assert stats["long_rows"] == (1 if m > LONG_RUN else 0)
+    assert stats["long_items"] == (m if m > LONG_RUN else 0)
     log("hot row", m, stats, c.compare(f"hot{m}"))
     c.check_invariant()
 
@@ -94,7 +96,7 @@ def test_hot_rows_share_a_stripe():
     """Two long runs and one short run in the same stripe, plus a long run at the very end."""
     R, D, k, S = 64, 128, 4, 5
     rng = np.random.default_rng(0)
-    keys = np.concatenate([np.full(3000, 8), np.full(700, 9), np.full(5, 11), np.full(1000, 63),
+    keys = np.concatenate([np.full(3000, 8), np.full(1700, 9), np.full(5, 11), np.full(1500, 63),
                            rng.integers(0, R, 2000)]).astype(np.uint64)
     rng.shuffle(keys)
     c = Case(R, D, k, S, max_batch=len(keys), seed=29)

@@ -30,7 +30,7 @@ def test_gradient_propagation_shapes(opt, R, D, k, S, n):
 
 
 @pytest.mark.parametrize("opt", [0, 1], ids=["adagrad", "momentum"])
-@pytest.mark.parametrize("m", [257, 5000, 200000])
+@pytest.mark.parametrize("m", [1025, 5000, 200000])
 def test_gradient_propagation_hot_stripe(opt, m):
     # all updates fall on the k rows of one stripe: the parity's chain is the long one (split-chain path)
     R, D, k, S = 1 << 10, 128, 4, 5

@@ -29,13 +29,13 @@ def test_rule_shapes(opt, comb, R, D, k, S, n):
 
 
 @pytest.mark.parametrize("opt,comb", RULES, ids=IDS)
-@pytest.mark.parametrize("m", [1, 256, 257, 5000, 200000])
+@pytest.mark.parametrize("m", [1, 256, 257, 1024, 1025, 5000, 200000])
 def test_rule_one_hot_row(opt, comb, m):
     R, D, k, S = 1 << 10, 128, 4, 5
     c = _case(R, D, k, S, m, opt, comb, seed=67)
     c.update(np.full(m, 321, np.uint64), grads_for(67, 0, m, D))
     stats = c.ctx.batch_stats()
-    assert stats["long_rows"] == (1 if m > 256 else 0)
+    assert stats["long_rows"] == (1 if m > 1024 else 0)
     log("hot row", (opt, comb, m), stats, c.compare(f"hot{m}"))
     c.check_invariant()
     ld = c.ld.cpu().numpy()
