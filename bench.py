@@ -322,15 +322,20 @@ def main():
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         ms, calls = [0.0, 0.0, (t1 - t0) * 1e3], args.steps      # no phase split: everything booked as one
+        step_ms = None
     else:
         ctx.profile(True)
         ctx.profile_read()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
+        marks[0].record()
         for i in range(args.steps):
             ctx.update(keys[i % nb], grads[i % nb])
+            marks[i + 1].record()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
+        step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
         ms, calls = ctx.profile_read()
         ctx.profile(False)
         assert calls == min(args.steps, 256)
@@ -359,6 +364,8 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
         "data": "synthetic",
+        "step_ms": None if not step_ms else {"median": step_ms[len(step_ms) // 2], "best": step_ms[0],
+                                             "worst": step_ms[-1]},
         "config": {"workload": f"{args.workload}" + (f">>{sh}" if sh else "") + variant, "items_per_step": per,
                    "rows": R, "dim": D, "k": k, "servers": S, "storage": "f32", "optimizer": args.optimizer, "combine": bool(args.combine),
                    "keys": w["kind"], "batches_resident": nb, "hip_graph": bool(args.graph)},
@@ -473,10 +480,15 @@ def main():
             nbatch += 1
             if cpu_s * threads > 20.0 or nbatch == 4:
                 break
+        n1 = min(len(hk), 1 << 16)                      # the same oracle on one thread, on a slice of that sample
+        tc = time.perf_counter()
+        oracle.update(hE, hA, hPE, hPA, k, S, si.DEFAULT_LR, si.DEFAULT_EPS, hk[:n1], hg[:n1], hld, hlp, threads=1)
+        one_s = time.perf_counter() - tc
         out["cpu_baseline"] = {"value": cpu_items / cpu_s, "unit": "items/s", "cores": threads, "kind": "oracle",
                                "sample": f"rows [0,{shard_rows}) (1/16 of the stripes) of the same tables and all "
                                          f"their updates from the first {nbatch} batches: {cpu_items} items, "
-                                         f"{cpu_s:.2f}s wall"}
+                                         f"{cpu_s:.2f}s wall",
+                               "single_thread_value": n1 / one_s, "host_cpus": os.cpu_count()}
     print(json.dumps(out), flush=True)
 
 
