@@ -99,6 +99,19 @@ __global__ __launch_bounds__(256) void recover_server_kernel(float *E, float *A,
     }
 }
 
+// The encoder (Sec. 3.2 "Encoder and decoder"; run once before training, Sec. 3.1) is the same walk
+// with every stripe's parity as the unit to build: PE[g] = sum_j E[k*g+j], PA likewise, summed in
+// fp64 by increasing j and rounded once.
+__global__ __launch_bounds__(256) void encode_kernel(const float *E, const float *A, float *PE, float *PA, uint32_t stripes,
+                                                     uint32_t D, uint32_t k)
+{
+    const uint32_t w0 = (blockIdx.x * blockDim.x + threadIdx.x) / kWave, nw = (gridDim.x * blockDim.x) / kWave;
+    for (uint32_t g = w0; g < stripes; g += nw) {
+        rebuild_row(const_cast<float *>(E), PE, g, (int)k, D, k);
+        rebuild_row(const_cast<float *>(A), PA, g, (int)k, D, k);
+    }
+}
+
 __device__ __forceinline__ void read_row(const float *T, const float *P, uint32_t x, uint32_t g, uint32_t j, bool decode,
                                          float *out, size_t i, uint32_t D, uint32_t k)
 {
@@ -139,6 +152,12 @@ __global__ __launch_bounds__(256) void degraded_read_kernel(const float *E, cons
         read_row(E, PE, x, g, j, decode, out_E, i, D, k);
         if (out_A) read_row(A, PA, x, g, j, decode, out_A, i, D, k);
     }
+}
+
+void launch_encode(const Geometry &g, const float *E, const float *A, float *PE, float *PA,
+                   int grid_blocks, hipStream_t st)
+{
+    hipLaunchKernelGGL(encode_kernel, dim3(grid_blocks), dim3(256), 0, st, E, A, PE, PA, g.rows / g.k, g.D, g.k);
 }
 
 void launch_fail_server(const Geometry &g, float *E, float *A, float *PE, float *PA, uint32_t server,

@@ -893,41 +893,8 @@ __global__ __launch_bounds__(256) void count_rows_kernel(const uint32_t *sk, uin
 }
 
 // ================================================================================================
-// encode and route
+// route
 // ================================================================================================
-
-struct D4 { double v[4]; };
-__device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
-__device__ __forceinline__ void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
-__device__ __forceinline__ D4 widen4(float4 f) { return D4{{(double)f.x, (double)f.y, (double)f.z, (double)f.w}}; }
-__device__ __forceinline__ float4 narrow4(const D4 &d)
-{
-    return float4{(float)d.v[0], (float)d.v[1], (float)d.v[2], (float)d.v[3]};
-}
-
-__global__ __launch_bounds__(256) void encode_kernel(const float *E, const float *A, float *PE, float *PA,
-                                                     uint32_t stripes, uint32_t D, uint32_t k)
-{
-    const uint32_t d4 = D / 4;
-    const size_t total = (size_t)stripes * d4;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += stride) {
-        const size_t g = t / d4;
-        const uint32_t col = (uint32_t)(t - g * d4) * 4u;
-        D4 se = D4{{0, 0, 0, 0}}, sa = D4{{0, 0, 0, 0}};
-        for (uint32_t j = 0; j < k; ++j) {
-            const D4 e = widen4(ld4(E + (g * k + j) * D + col));
-            const D4 s = widen4(ld4(A + (g * k + j) * D + col));
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                se.v[q] += e.v[q];
-                sa.v[q] += s.v[q];
-            }
-        }
-        st4(PE + g * D + col, narrow4(se));
-        st4(PA + g * D + col, narrow4(sa));
-    }
-}
 
 __global__ __launch_bounds__(256) void route_kernel(const uint64_t *keys, uint64_t n, uint64_t rows, uint32_t k,
                                                     uint32_t S, uint64_t *stripe, uint32_t *member,
@@ -1056,12 +1023,6 @@ void launch_apply(const Scratch &s, const Geometry &g, float *E, float *A, float
     ECRM_DISPATCH(apply_for, a, parity, cus, st);
 }
 #undef ECRM_DISPATCH
-
-void launch_encode(const Geometry &g, const float *E, const float *A, float *PE, float *PA,
-                   int grid_blocks, hipStream_t st)
-{
-    hipLaunchKernelGGL(encode_kernel, dim3(grid_blocks), dim3(256), 0, st, E, A, PE, PA, g.rows / g.k, g.D, g.k);
-}
 
 void launch_route(const Scratch &s, const Geometry &g, const uint64_t *keys, uint64_t n, uint64_t *stripe,
                   uint32_t *member, uint32_t *data_srv, uint32_t *parity_srv, hipStream_t st)
