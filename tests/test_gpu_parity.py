@@ -69,6 +69,9 @@ def test_medium_workload():
     (64 * 20, 1024, 64, 65, 2000),      # maximum D and k
     (4 * 64, 200, 4, 8, 70000),         # few rows, many duplicates per row (runs of ~270)
     (1 << 16, 128, 4, 5, 1),            # a single update
+    (1000, 128, 1, 2, 5000),            # k = 1: the parity is a mirror of the entry
+    (4 * 700, 128, 4, 1024, 9000),      # the largest number of servers
+    (2 * 333, 8, 2, 3, 40000),          # very short rows, long runs (~60 updates per entry)
 ])
 def test_shapes(R, D, k, S, n):
     c = Case(R, D, k, S, max_batch=n, seed=17)

@@ -20,7 +20,8 @@ def _trained_case(R, D, k, S, n, seed):
 
 
 @pytest.mark.parametrize("R,D,k,S", [(4 * 2000, 128, 4, 5), (2 * 1500, 128, 2, 5), (10 * 300, 256, 10, 11),
-                                     (3 * 700, 36, 3, 4), (64 * 20, 1024, 64, 65), (4 * 100, 4, 4, 9)])
+                                     (3 * 700, 36, 3, 4), (64 * 20, 1024, 64, 65), (4 * 100, 4, 4, 9),
+                                     (500, 128, 1, 2)])
 def test_fail_and_recover_every_server(R, D, k, S):
     c = _trained_case(R, D, k, S, 20000, seed=51)
     for server in range(S):
