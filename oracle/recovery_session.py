@@ -68,6 +68,42 @@ class RecoverySession:
         self._apply(np.ascontiguousarray(keys[~h]), np.ascontiguousarray(grads[~h]))
         return True
 
+    # -- what a worker reads meanwhile ------------------------------------------------------------
+    def read(self, keys):
+        """Entries and their state as a worker sees them during the recovery (Sec. 3.4: a worker that
+        reads an updated but locked entry reads it from the buffer).  Reading taken here: the value
+        is the one the entry will have once its waiting updates have been replayed, i.e. the stored
+        entry with the buffered updates of that entry applied in arrival order; an entry that the
+        failed server held and that is not rebuilt yet is first decoded from its stripe.  Nothing is
+        modified."""
+        keys = np.asarray(keys, np.uint64)
+        D = self.E.shape[1]
+        outE, outA = np.empty((len(keys), D), np.float32), np.empty((len(keys), D), np.float32)
+        held = self.held(keys)
+        k, S, s = np.uint64(self.k), np.uint64(self.S), np.uint64(self.server)
+        for i, x in enumerate(keys):
+            g, j = x // k, x % k
+            member_here = (s + S - (g + np.uint64(1)) % S) % S
+            lost_unbuilt = (self.active and g % S != s and member_here == j
+                            and g // np.uint64(self.spc) >= np.uint64(self.next))
+            if lost_unbuilt:
+                e, a = oracle.degraded_read(self.E, self.A, self.PE, self.PA, self.k, self.S,
+                                            np.array([x], np.uint64), self.server)
+                e, a = e.copy(), a.copy()
+            else:
+                e, a = self.E[int(x):int(x) + 1].copy(), self.A[int(x):int(x) + 1].copy()
+            if held[i]:
+                sel = self.buf_keys == x
+                if sel.any():
+                    # the entry alone in a table of its own: the oracle's update rule on its waiting updates
+                    pe, pa = e.copy(), a.copy()
+                    oracle.update_rule(e, a, pe, pa, 1, 2, self.lr, self.eps, self.momentum, self.optimizer,
+                                       self.combine, np.zeros(int(sel.sum()), np.uint64),
+                                       np.ascontiguousarray(self.buf_grads[sel]), np.zeros(2, np.uint64),
+                                       np.zeros(2, np.uint64))
+            outE[i], outA[i] = e[0], a[0]
+        return outE, outA
+
     # -- the recovery process ---------------------------------------------------------------------
     def lock(self):
         assert self.active and not self.locked and self.next < self.chunks

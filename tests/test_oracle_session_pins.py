@@ -97,3 +97,99 @@ def test_full_buffer_rejects_the_batch():
     assert not ses.update(keys, grads)
     np.testing.assert_array_equal(E, E0)
     assert len(ses.buf_keys) == 0
+
+
+# ---- reads during the recovery (Sec. 3.4: a locked, updated entry is read from the buffer) -------
+
+def _reference_after(E0, A0, PE0, PA0, k, S, server, batches):
+    """fail, rebuild everything at once, then apply the batches: what a worker should see"""
+    rE, rA, rPE, rPA = E0.copy(), A0.copy(), PE0.copy(), PA0.copy()
+    oracle.fail_server(rE, rA, rPE, rPA, k, S, server)
+    oracle.recover_server(rE, rA, rPE, rPA, k, S, server)
+    for kk, gg in batches:
+        oracle.update(rE, rA, rPE, rPA, k, S, 0.01, 1e-8, kk, gg)
+    return rE, rA
+
+
+@pytest.mark.parametrize("chunks", [1, 4])
+def test_a_reader_never_notices_the_recovery(chunks):
+    """At every point of the protocol -- before a lock, under it, after the decode, after the unlock --
+    reading all entries gives what training without a failure would have given (to the roundings of
+    the stored sums): waiting updates are seen, lost entries are decoded, nothing is seen twice."""
+    k, S, R, D, server = 4, 5, 4 * 40, 8, 2
+    rng, E, A, PE, PA = _setup(R, D, k, S, seed=77 + chunks)
+    E0, A0, PE0, PA0 = E.copy(), A.copy(), PE.copy(), PA.copy()
+    oracle.fail_server(E, A, PE, PA, k, S, server)
+    ses = RecoverySession(E, A, PE, PA, k, S, 0.01, 1e-8, server, chunks, capacity=10 ** 6)
+    allkeys = np.arange(R, dtype=np.uint64)
+    done, saw_waiting = [], False
+
+    def check():
+        rE, rA = _reference_after(E0, A0, PE0, PA0, k, S, server, done)
+        gE, gA = ses.read(allkeys)
+        np.testing.assert_allclose(gE, rE, rtol=1e-4, atol=5e-6)
+        np.testing.assert_allclose(gA, rA, rtol=1e-4, atol=2e-9)
+
+    check()
+    for c in range(ses.chunks):
+        for stage in ("before", "locked", "decoded"):
+            if stage == "locked":
+                ses.lock()
+            if stage == "decoded":
+                ses.decode()
+            b = _batch(rng, R, D, 300, hot=np.uint64(5))
+            assert ses.update(*b)
+            done.append(b)
+            saw_waiting |= len(ses.buf_keys) > 0
+            check()
+        ses.unlock()
+        check()
+    assert saw_waiting and not ses.active
+
+
+def test_read_before_unlock_is_the_entry_after_unlock():
+    """The value read from the buffer is bit for bit the one the replay writes."""
+    k, S, R, D, server = 4, 5, 4 * 30, 4, 0
+    rng, E, A, PE, PA = _setup(R, D, k, S, seed=5)
+    oracle.fail_server(E, A, PE, PA, k, S, server)
+    ses = RecoverySession(E, A, PE, PA, k, S, 0.01, 1e-8, server, chunks=3, capacity=10 ** 6)
+    allkeys = np.arange(R, dtype=np.uint64)
+    for c in range(ses.chunks):
+        ses.lock()
+        assert ses.update(*_batch(rng, R, D, 500))
+        ses.decode()
+        assert ses.update(*_batch(rng, R, D, 500))
+        before_E, before_A = ses.read(allkeys)
+        ses.unlock()
+        after_E, after_A = ses.read(allkeys)
+        np.testing.assert_array_equal(before_E, after_E)
+        np.testing.assert_array_equal(before_A, after_A)
+        lo, hi = c * ses.spc * k, min((c + 1) * ses.spc * k, R)       # the released chunk is now in the tables
+        np.testing.assert_array_equal(E[lo:hi], after_E[lo:hi])
+        np.testing.assert_array_equal(A[lo:hi], after_A[lo:hi])
+
+
+def test_read_without_waiting_updates_is_the_table_or_the_decoded_entry():
+    k, S, R, D, server = 2, 5, 2 * 40, 4, 3
+    rng, E, A, PE, PA = _setup(R, D, k, S, seed=6)
+    E0 = E.copy()
+    oracle.fail_server(E, A, PE, PA, k, S, server)
+    ses = RecoverySession(E, A, PE, PA, k, S, 0.01, 1e-8, server, chunks=2, capacity=10)
+    allkeys = np.arange(R, dtype=np.uint64)
+    gE, _ = ses.read(allkeys)
+    _, _, ds, _ = oracle.route(allkeys, R, k, S)
+    lost = ds == server
+    assert lost.any() and np.isnan(E[lost]).all()
+    np.testing.assert_array_equal(gE[~lost], E0[~lost])                   # survivors: the table itself
+    np.testing.assert_allclose(gE[lost], E0[lost], rtol=0, atol=2e-7)     # lost ones: decoded, to one rounding of the sum
+    for m in ("optimizer", "combine"):                                    # the other rules go through the same door
+        ses2 = RecoverySession(E.copy(), A.copy(), PE.copy(), PA.copy(), k, S, 0.01, 1e-8, server, 2, 100,
+                               optimizer=1 if m == "optimizer" else 0, momentum=0.9, combine=1 if m == "combine" else 0)
+        ses2.lock()
+        kk, gg = _batch(rng, R, D, 50)
+        assert ses2.update(kk, gg)
+        rE, rA = ses2.read(allkeys)
+        ses2.decode()
+        ses2.unlock()
+        r2E, r2A = ses2.read(allkeys)
+        np.testing.assert_array_equal(rE, r2E)
