@@ -169,7 +169,8 @@ int ecrm_degraded_read(ecrm_ctx *ctx, const uint64_t *keys, uint64_t n, uint32_t
  *   ecrm_recovery_state   waits for the stream; reports whether a recovery is active, the number of
  *                         chunks rebuilt, the number of chunks, and how many updates are waiting.
  * A batch whose held-back items do not fit the buffer is rejected as a whole (sticky EBUFFER).
- * Reads of entries whose updates are waiting return the entry without them. */
+ * ecrm_degraded_read returns entries whose updates are waiting without them; ecrm_recovery_read
+ * (below) returns them with the waiting updates applied. */
 int ecrm_recovery_begin(ecrm_ctx *ctx, uint32_t server, uint32_t chunks, uint64_t *buf_keys, float *buf_grads,
                         uint64_t capacity, void *hip_stream);
 int ecrm_recovery_lock(ecrm_ctx *ctx);
@@ -177,6 +178,17 @@ int ecrm_recovery_decode(ecrm_ctx *ctx, void *hip_stream);
 int ecrm_recovery_unlock(ecrm_ctx *ctx, void *hip_stream);
 int ecrm_recovery_state(ecrm_ctx *ctx, void *hip_stream, uint32_t *active, uint32_t *next_chunk, uint32_t *chunks,
                         uint64_t *buffered);
+
+/* What a worker reads while a recovery is in progress (Sec. 3.4: "workers reading an updated, but
+ * locked entry do so by reading from the buffer"): out_E[i][0..D) (and out_A[i] if not NULL) receive
+ * entry keys[i] with its waiting updates applied in arrival order -- the value it will have once they
+ * are replayed; an entry that the failed server held and that is not rebuilt yet is decoded from its
+ * stripe first.  Nothing is modified, so the read may be repeated.  Call it on the update stream.
+ * While a recovery is active the call SYNCHRONISES the stream (it has to learn how many updates are
+ * waiting) and uses the scratch buffer to group them by entry; without one it is a plain gather and
+ * only enqueues.  Keys >= rows raise the sticky EKEYRANGE status and leave their rows unwritten. */
+int ecrm_recovery_read(ecrm_ctx *ctx, const uint64_t *keys, uint64_t n, float *out_E, float *out_A,
+                       void *hip_stream);
 
 /* Waits for the stream, then returns ECRM_OK, or EKEYRANGE if any batch since the last
  * ecrm_clear_status (or bind) carried a bad key, EBUFFER if one overflowed the recovery buffer, or

@@ -22,7 +22,7 @@ SYMBOLS = ["ecrm_create", "ecrm_destroy", "ecrm_data_bytes", "ecrm_parity_bytes"
            "ecrm_profile", "ecrm_profile_read", "ecrm_batch_stats", "ecrm_strerror",
            "ecrm_fail_server", "ecrm_recover_server", "ecrm_degraded_read",
            "ecrm_recovery_begin", "ecrm_recovery_lock", "ecrm_recovery_decode", "ecrm_recovery_unlock",
-           "ecrm_recovery_state"]
+           "ecrm_recovery_state", "ecrm_recovery_read"]
 
 
 class EcrmConfig(C.Structure):
@@ -63,6 +63,7 @@ def load_library():
         lib.ecrm_recover_server.argtypes = [vp, C.c_uint32, vp]
         lib.ecrm_degraded_read.argtypes = [vp, u64p, C.c_uint64, C.c_uint32, f32p, f32p, vp]
         lib.ecrm_recovery_begin.argtypes = [vp, C.c_uint32, C.c_uint32, u64p, f32p, C.c_uint64, vp]
+        lib.ecrm_recovery_read.argtypes = [vp, u64p, C.c_uint64, f32p, f32p, vp]
         lib.ecrm_recovery_lock.argtypes = [vp]
         lib.ecrm_recovery_decode.argtypes = [vp, vp]
         lib.ecrm_recovery_unlock.argtypes = [vp, vp]
@@ -184,6 +185,13 @@ class Ecrm:
                                           _ptr(out_E), _ptr(out_A), _stream(stream))
         if check and rc != ECRM_OK:
             raise EcrmError(rc, "ecrm_degraded_read")
+        return rc
+
+    def recovery_read(self, keys, out_E, out_A=None, stream=None, check=True):
+        rc = self._lib.ecrm_recovery_read(self._ctx, _ptr(keys), C.c_uint64(keys.numel()), _ptr(out_E), _ptr(out_A),
+                                          _stream(stream))
+        if check and rc != ECRM_OK:
+            raise EcrmError(rc, "ecrm_recovery_read")
         return rc
 
     def recovery_begin(self, server, chunks, buf_keys, buf_grads, capacity, stream=None, check=True):

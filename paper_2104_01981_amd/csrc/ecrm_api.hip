@@ -348,6 +348,35 @@ int ecrm_recovery_state(ecrm_ctx *c, void *stream, uint32_t *active, uint32_t *n
     return ECRM_OK;
 }
 
+int ecrm_recovery_read(ecrm_ctx *c, const uint64_t *keys, uint64_t n, float *out_E, float *out_A, void *stream)
+{
+    if (!c) return ECRM_EINVAL;
+    if (!c->bound) return ECRM_ENOTBOUND;
+    if (n == 0) return ECRM_OK;
+    if (!aligned(keys, 8) || !aligned(out_E, 16) || (out_A && !aligned(out_A, 16))) return ECRM_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    init_if_needed(c, st);
+    if (!c->rv.active) {                       // no recovery in progress: a plain gather
+        launch_degraded_read(c->s, c->geo, c->E, c->A, c->PE, c->PA, keys, n, ECRM_NO_SERVER, out_E, out_A,
+                             c->grid_blocks, st);
+        return check_launch();
+    }
+    // how many updates are waiting (the grouping below is sized by it)
+    if (hipStreamSynchronize(st) != hipSuccess) return ECRM_EHIP;
+    Header h;
+    if (hipMemcpy(&h, c->s.hdr, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return ECRM_EHIP;
+    const uint32_t m = h.buf_count;
+    uint32_t *bk = nullptr, *bi = nullptr;
+    if (m) {
+        RecoveryView none;
+        memset(&none, 0, sizeof(none));
+        launch_sort(c->s, c->geo, none, (const uint64_t *)c->buf_keys[c->buf_cur], m, c->key_bits, 1u, false, &bk, &bi, st);
+    }
+    launch_recovery_read(c->s, c->geo, c->rv, c->E, c->A, c->PE, c->PA, keys, n, bk, bi, m, c->buf_grads[c->buf_cur],
+                         out_E, out_A, c->grid_blocks, st);
+    return check_launch();
+}
+
 int ecrm_fail_server(ecrm_ctx *c, uint32_t server, void *stream)
 {
     if (!c) return ECRM_EINVAL;

@@ -117,6 +117,10 @@ void launch_encode(const Geometry &g, const float *E, const float *A, float *PE,
                    int grid_blocks, hipStream_t st);
 void launch_route(const Scratch &s, const Geometry &g, const uint64_t *keys, uint64_t n, uint64_t *stripe,
                   uint32_t *member, uint32_t *data_srv, uint32_t *parity_srv, hipStream_t st);
+void launch_recovery_read(const Scratch &s, const Geometry &g, const RecoveryView &rv, const float *E, const float *A,
+                          const float *PE, const float *PA, const uint64_t *keys, uint64_t n, const uint32_t *bk,
+                          const uint32_t *bi, uint32_t m, const float *buf_grads, float *out_E, float *out_A,
+                          int grid_blocks, hipStream_t st);
 void launch_clear_status(const Scratch &s, hipStream_t st);
 void launch_fail_server(const Geometry &g, float *E, float *A, float *PE, float *PA, uint32_t server,
                         int grid_blocks, hipStream_t st);

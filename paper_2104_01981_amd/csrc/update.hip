@@ -893,6 +893,98 @@ __global__ __launch_bounds__(256) void count_rows_kernel(const uint32_t *sk, uin
 }
 
 // ================================================================================================
+// reads while a server is being recovered
+// ================================================================================================
+
+// Sec. 3.4 "Training during recovery": a worker that reads an updated but locked entry reads it from
+// the buffer.  The buffer here holds updates, not entries, so the read applies them: the value
+// returned is the stored entry with its waiting updates applied in arrival order -- what the entry
+// will be once they have been replayed -- and an entry the failed server held that is not rebuilt
+// yet is first decoded from its stripe (parity minus the other members, by increasing member, rounded
+// to fp32 as the decoder stores it).  The waiting updates come grouped by entry (bk sorted, bi their
+// positions in the buffer).  One wave per requested key; nothing is modified.
+struct ReadArgs {
+    const float *E, *A, *PE, *PA;
+    const uint64_t *keys;
+    uint64_t n;
+    const uint32_t *bk, *bi;
+    uint32_t m;
+    const float *buf_grads;
+    float *out_E, *out_A;
+    Header *hdr;
+    RecoveryView rv;
+    Geometry geo;
+};
+
+template <int MODE>
+__global__ __launch_bounds__(256) void recovery_read_kernel(ReadArgs a)
+{
+    const uint32_t D = a.geo.D, k = a.geo.k, S = a.geo.S, lane = lane_id();
+    const RuleParams rp = rule_params(a.geo);
+    const uint64_t nw = wave_count();
+    for (uint64_t i = wave_id(); i < a.n; i += nw) {
+        const uint64_t key = a.keys[i];
+        const uint32_t khi = uniform((uint32_t)(key >> 32)), x = uniform((uint32_t)key);
+        if (khi != 0 || x >= a.geo.rows) {
+            if (lane == 0) atomicOr(&a.hdr->err_sticky, 1u);
+            continue;
+        }
+        const uint32_t g = x / k, j = x - g * k;
+        bool decode = false;                      // the entry the failed server held, not rebuilt yet
+        if (a.rv.active) {
+            const uint32_t p = g % S;
+            if (p != a.rv.server) {
+                const uint32_t lost = (a.rv.server + S - (p + 1u) % S) % S;
+                decode = lost == j && g / a.rv.stripes_per_chunk >= a.rv.next;
+            }
+        }
+        uint32_t lo = a.m;                        // first waiting update of x, if it can have any
+        if (a.m && held_back(a.rv, x, k, S)) {
+            uint32_t l = 0, h = a.m;
+            while (l < h) {
+                const uint32_t mid = l + (h - l) / 2;
+                if (uniform(a.bk[mid]) < x) l = mid + 1; else h = mid;
+            }
+            lo = l;
+        }
+        for (uint32_t col0 = 0; col0 < D; col0 += 128u) {
+            D2 e, s0;
+            if (decode) {
+                e = widen2(ld2<0>(row_f32(a.PE, g, D, col0), 0));
+                s0 = widen2(ld2<0>(row_f32(a.PA, g, D, col0), 0));
+                for (uint32_t mth = 0; mth < k; ++mth) {
+                    if (mth == j) continue;
+                    const D2 ve = widen2(ld2<0>(row_f32(a.E, g * k + mth, D, col0), 0));
+                    const D2 vs = widen2(ld2<0>(row_f32(a.A, g * k + mth, D, col0), 0));
+                    e.x -= ve.x; e.y -= ve.y;
+                    s0.x -= vs.x; s0.y -= vs.y;
+                }
+                e = widen2(narrow2(e));
+                s0 = widen2(narrow2(s0));
+            } else {
+                e = widen2(ld2<0>(row_f32(a.E, x, D, col0), 0));
+                s0 = widen2(ld2<0>(row_f32(a.A, x, D, col0), 0));
+            }
+            D2 G = start2<MODE>(s0), acc = D2{0, 0};
+            bool any = false;
+            for (uint32_t pos = lo; pos < a.m; ++pos) {
+                if (uniform(a.bk[pos]) != x) break;
+                const float2 gr = ld2<0>(row_f32(a.buf_grads, uniform(a.bi[pos]), D, col0), 0);
+                item2<MODE>(G, acc, gr, rp);
+                any = true;
+            }
+            if (any) finish2<MODE>(G, acc, s0, rp); else G = s0;
+            const rsrc_t oe = __builtin_amdgcn_make_buffer_rsrc(a.out_E + (size_t)i * D + col0, 0, (int)((D - col0) * 4u), kRsrcFlags);
+            st2(oe, 0, narrow2(D2{e.x - acc.x, e.y - acc.y}));
+            if (a.out_A) {
+                const rsrc_t oa = __builtin_amdgcn_make_buffer_rsrc(a.out_A + (size_t)i * D + col0, 0, (int)((D - col0) * 4u), kRsrcFlags);
+                st2(oa, 0, narrow2(G));
+            }
+        }
+    }
+}
+
+// ================================================================================================
 // route
 // ================================================================================================
 
@@ -1023,6 +1115,24 @@ void launch_apply(const Scratch &s, const Geometry &g, float *E, float *A, float
     ECRM_DISPATCH(apply_for, a, parity, cus, st);
 }
 #undef ECRM_DISPATCH
+
+void launch_recovery_read(const Scratch &s, const Geometry &g, const RecoveryView &rv, const float *E, const float *A,
+                          const float *PE, const float *PA, const uint64_t *keys, uint64_t n, const uint32_t *bk,
+                          const uint32_t *bi, uint32_t m, const float *buf_grads, float *out_E, float *out_A,
+                          int grid_blocks, hipStream_t st)
+{
+    ReadArgs a;
+    a.E = E; a.A = A; a.PE = PE; a.PA = PA;
+    a.keys = keys; a.n = n; a.bk = bk; a.bi = bi; a.m = m; a.buf_grads = buf_grads;
+    a.out_E = out_E; a.out_A = out_A; a.hdr = s.hdr; a.rv = rv; a.geo = g;
+    const dim3 grid(grid_blocks), block(256);
+    switch (g.mode) {
+        case kAdagradSeq: hipLaunchKernelGGL(recovery_read_kernel<kAdagradSeq>, grid, block, 0, st, a); break;
+        case kMomentumSeq: hipLaunchKernelGGL(recovery_read_kernel<kMomentumSeq>, grid, block, 0, st, a); break;
+        case kAdagradCombine: hipLaunchKernelGGL(recovery_read_kernel<kAdagradCombine>, grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL(recovery_read_kernel<kMomentumCombine>, grid, block, 0, st, a); break;
+    }
+}
 
 void launch_route(const Scratch &s, const Geometry &g, const uint64_t *keys, uint64_t n, uint64_t *stripe,
                   uint32_t *member, uint32_t *data_srv, uint32_t *parity_srv, hipStream_t st)

@@ -113,3 +113,88 @@ def test_recovery_buffer_overflow_and_state_errors():
     c.ctx.update(torch.from_numpy(small.view(np.int64)).cuda(), g[:10].contiguous())
     assert c.ctx.status() == 0
     assert 0 < c.ctx.recovery_state()["buffered"] <= 10
+
+
+@pytest.mark.parametrize("chunks", [1, 4])
+@pytest.mark.parametrize("R,D,k,S,server,opt,comb", [(4 * 3000, 128, 4, 5, 2, 0, 0), (10 * 400, 256, 10, 11, 7, 1, 0),
+                                                      (2 * 2500, 36, 2, 5, 0, 0, 1)])
+def test_reads_during_recovery(chunks, R, D, k, S, server, opt, comb):
+    """ecrm_recovery_read against the protocol oracle's read at every stage (before a lock, under it,
+    after the decode, after the unlock), and against the tables the replay leaves behind."""
+    n, seed = 12000, 97
+    cap = 8 * n
+    c = Case(R, D, k, S, max_batch=cap, seed=seed, optimizer=opt, momentum=0.9, combine=comb)
+    st, mem, ds, ps = oracle.route(np.arange(R, dtype=np.uint64), R, k, S)
+    lost_rows = np.nonzero(ds == server)[0]
+    hot = [int(lost_rows[3]), int(lost_rows[len(lost_rows) // 2]), 5, int(lost_rows[-1]), R - 1]
+    first = 0
+    keys, g = _batch(seed, first, n, R, D, hot)
+    c.update(keys, g)
+    first += n
+    c.ctx.fail_server(server)
+    oracle.fail_server(c.hE, c.hA, c.hPE, c.hPA, k, S, server)
+    buf_keys = torch.empty(2 * cap, dtype=torch.int64, device="cuda")
+    buf_grads = torch.empty(2 * cap, D, device="cuda")
+    c.ctx.recovery_begin(server, chunks, buf_keys, buf_grads, cap)
+    ses = RecoverySession(c.hE, c.hA, c.hPE, c.hPA, k, S, c.lr, c.eps, server, chunks, cap, c.hld, c.hlp,
+                          optimizer=opt, momentum=0.9, combine=comb, threads=8)
+    rng = np.random.default_rng(1)
+    sample = np.unique(np.concatenate([np.array(hot), rng.integers(0, R, 120), rng.choice(lost_rows, 80),
+                                       np.arange(0, min(R, 40 * k))])).astype(np.uint64)
+    sample_t = torch.from_numpy(sample.view(np.int64)).cuda()
+    oe = torch.empty(len(sample), D, device="cuda")
+    oa = torch.empty(len(sample), D, device="cuda")
+
+    def both_update():
+        nonlocal first
+        keys, g = _batch(seed, first, n, R, D, hot)
+        first += n
+        c.ctx.update(torch.from_numpy(keys.view(np.int64)).cuda(), g)
+        assert ses.update(keys, g.cpu().numpy())
+
+    def both_read(stage):
+        c.ctx.recovery_read(sample_t, oe, oa)
+        hE, hA = ses.read(sample)
+        assert c.ctx.status() == 0
+        assert not bool(torch.isnan(oe).any())
+        np.testing.assert_allclose(oe.cpu().numpy(), hE, rtol=1e-4, atol=5e-6, err_msg=stage)
+        np.testing.assert_allclose(oa.cpu().numpy(), hA, rtol=1e-4, atol=2e-9, err_msg=stage)
+
+    both_read("right after the failure")
+    for ch in range(ses.chunks):
+        both_update()
+        both_read(f"chunk {ch}: before the lock")
+        c.ctx.recovery_lock()
+        ses.lock()
+        both_update()
+        both_read(f"chunk {ch}: locked")
+        c.ctx.recovery_decode()
+        ses.decode()
+        both_update()
+        both_read(f"chunk {ch}: decoded")
+        seen_e, seen_a = oe.clone(), oa.clone()
+        c.ctx.recovery_unlock()
+        ses.unlock()
+        both_read(f"chunk {ch}: released")
+        # what was read from the buffer is what the replay wrote (a long chain is summed piecewise there)
+        assert torch.allclose(seen_e, oe, rtol=1e-6, atol=1e-9) and torch.allclose(seen_a, oa, rtol=1e-6, atol=1e-12)
+        assert int((seen_e != oe).sum()) <= 1e-3 * oe.numel()
+        lo, hi = ch * ses.spc * k, min((ch + 1) * ses.spc * k, R)
+        inside = torch.from_numpy(((sample >= lo) & (sample < hi))).cuda()
+        rows = sample_t[inside]
+        assert torch.equal(c.E[rows], oe[inside]) and torch.equal(c.A[rows], oa[inside])
+    assert not c.ctx.recovery_state()["active"]
+    both_update()
+    both_read("after the recovery")                     # a plain gather again
+    assert torch.equal(c.E[sample_t], oe)
+    log("reads during recovery", (chunks, R, D, k, S, server, opt, comb), c.compare("session reads"))
+
+
+def test_recovery_read_errors():
+    c = Case(4 * 100, 128, 4, 5, max_batch=100, seed=3)
+    kt = torch.tensor([1, 2, 400], dtype=torch.int64, device="cuda")
+    oe = torch.full((3, 128), 7.0, device="cuda")
+    c.ctx.recovery_read(kt, oe)
+    assert c.ctx.status() == -5                          # a key >= rows
+    assert torch.equal(oe[0], c.E[1]) and torch.equal(oe[1], c.E[2]) and bool((oe[2] == 7.0).all())
+    c.ctx.clear_status()
