@@ -38,6 +38,23 @@ struct ecrm_ctx {
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// The multiply-and-shift division against the real one, around every place where it could go wrong
+// (multiples of the divisor at both ends of the range) and on a spread of other values.
+static bool divider_ok(const Divider &v)
+{
+    const uint32_t d = v.d;
+    uint64_t probe = 0x9E3779B97F4A7C15ull;
+    for (uint32_t i = 0; i < 4096; ++i) {
+        probe = probe * 6364136223846793005ull + 1442695040888963407ull;
+        const uint32_t base = i < 64 ? i * d : i < 128 ? 0xFFFFFFFFu - (i - 64) * d : (uint32_t)(probe >> 32);
+        for (int delta = -1; delta <= 1; ++delta) {
+            const uint32_t n = base + (uint32_t)delta;
+            if (v.div(n) != n / d || v.mod(n) != n % d) return false;
+        }
+    }
+    return true;
+}
+
 static void layout(ecrm_ctx *c)
 {
     const size_t n = c->max_batch, D = c->geo.D;
@@ -104,6 +121,12 @@ int ecrm_create(const ecrm_config *cfg, ecrm_ctx **out)
     c->geo.eps = cfg->eps;
     c->geo.mu = cfg->optimizer == ECRM_OPT_MOMENTUM ? cfg->momentum : 0.0f;
     c->geo.mode = cfg->optimizer + 2u * cfg->combine;
+    c->geo.dk = make_divider(cfg->k);
+    c->geo.dS = make_divider(cfg->servers);
+    if (!divider_ok(c->geo.dk) || !divider_ok(c->geo.dS)) {
+        delete c;
+        return ECRM_EINVAL;
+    }
     c->key_bits = 1;
     while (c->key_bits < 32 && (1ull << c->key_bits) < cfg->rows) ++c->key_bits;
     c->max_batch = (uint32_t)cfg->max_batch;
@@ -222,7 +245,7 @@ static int run_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uin
         while (key_bits < 32 && (1ull << key_bits) <= c->cfg.rows) ++key_bits;
     const uint32_t prop = c->cfg.propagation;
     uint32_t *sk = nullptr, *si = nullptr;
-    launch_sort(c->s, c->geo, c->rv, keys, n32, key_bits, 1u, true, &sk, &si, st);
+    launch_sort(c->s, c->geo, c->rv, keys, n32, key_bits, false, true, &sk, &si, st);
     if (c->rv.active)
         launch_hold_back(c->s, c->geo, c->rv, keys, grads, n32, c->buf_keys[target], c->buf_grads[target], c->buf_cap, st);
     if (ev) (void)hipEventRecord(ev[1], st);
@@ -242,7 +265,7 @@ static int run_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uin
         while (bits < 32 && (1ull << bits) < c->cfg.rows / c->cfg.k) ++bits;
         if (ev) (void)hipEventRecord(ev[3], st);
         launch_reset(c->s, c->geo.S, n32, false, st);
-        launch_sort(c->s, c->geo, c->rv, keys, n32, bits, c->geo.k, false, &sk, &si, st);
+        launch_sort(c->s, c->geo, c->rv, keys, n32, bits, true, false, &sk, &si, st);
         if (ev) (void)hipEventRecord(ev[4], st);
         launch_chains(c->s, gp, c->PA, grads, sk, si, n32, c->max_slots, c->max_pieces, c->cus, st);
         if (ev) (void)hipEventRecord(ev[5], st);
@@ -274,11 +297,14 @@ int ecrm_recovery_begin(ecrm_ctx *c, uint32_t server, uint32_t chunks, uint64_t 
     const uint32_t stripes = c->geo.rows / c->geo.k;
     if (server >= c->geo.S || chunks < 1 || chunks > stripes) return ECRM_EINVAL;
     if (capacity < 1 || capacity > c->max_batch || !aligned(buf_keys, 8) || !aligned(buf_grads, 16)) return ECRM_EINVAL;
+    const Divider spc_div = make_divider((stripes + chunks - 1) / chunks);
+    if (!divider_ok(spc_div)) return ECRM_EINVAL;
     c->rv.active = 1;
     c->rv.server = server;
     c->rv.next = 0;
     c->rv.locked = 0;
     c->rv.stripes_per_chunk = (stripes + chunks - 1) / chunks;
+    c->rv.dspc = spc_div;
     c->rec_chunks = (stripes + c->rv.stripes_per_chunk - 1) / c->rv.stripes_per_chunk;
     c->buf_cap = (uint32_t)capacity;
     c->buf_cur = 0;
@@ -370,7 +396,7 @@ int ecrm_recovery_read(ecrm_ctx *c, const uint64_t *keys, uint64_t n, float *out
     if (m) {
         RecoveryView none;
         memset(&none, 0, sizeof(none));
-        launch_sort(c->s, c->geo, none, (const uint64_t *)c->buf_keys[c->buf_cur], m, c->key_bits, 1u, false, &bk, &bi, st);
+        launch_sort(c->s, c->geo, none, (const uint64_t *)c->buf_keys[c->buf_cur], m, c->key_bits, false, false, &bk, &bi, st);
     }
     launch_recovery_read(c->s, c->geo, c->rv, c->E, c->A, c->PE, c->PA, keys, n, bk, bi, m, c->buf_grads[c->buf_cur],
                          out_E, out_A, c->grid_blocks, st);

@@ -62,6 +62,36 @@ struct Scratch {           // device pointers carved out of the caller's scratch
     double *long_res;              // [max_slots][2][D]: sum of steps, final accumulator
 };
 
+// Division of 32-bit numbers by a divisor fixed for the life of a context (k, S, stripes per chunk):
+// multiply-high and two shifts instead of the long sequence a division by a run-time value costs --
+// the placement arithmetic runs once per item in four kernels while a recovery is in progress.
+// q = (t + ((n - t) >> s1)) >> s2 with t = hi32(m * n), m = floor(2^32 (2^l - d) / d) + 1,
+// l = ceil(log2 d), s1 = min(l, 1), s2 = max(l - 1, 0): exact for every 32-bit n.
+struct Divider {
+    uint32_t d, m, s1, s2;
+    __host__ __device__ __forceinline__ uint32_t div(uint32_t n) const
+    {
+#ifdef __HIP_DEVICE_COMPILE__
+        const uint32_t t = __umulhi(m, n);
+#else
+        const uint32_t t = (uint32_t)(((unsigned long long)m * n) >> 32);
+#endif
+        return (t + ((n - t) >> s1)) >> s2;
+    }
+    __host__ __device__ __forceinline__ uint32_t mod(uint32_t n) const { return n - div(n) * d; }
+};
+inline Divider make_divider(uint32_t d)
+{
+    uint32_t l = 0;
+    while (l < 32 && (1ull << l) < d) ++l;
+    Divider r;
+    r.d = d;
+    r.m = (uint32_t)(((1ull << 32) * ((1ull << l) - d)) / d + 1);
+    r.s1 = l < 1 ? l : 1;
+    r.s2 = l ? l - 1 : 0;
+    return r;
+}
+
 // What an update has to know about a recovery in progress (Sec. 3.4): stripes are split into
 // `chunks` equal ranges; chunks below `next` are rebuilt, chunk `next` is being rebuilt if `locked`.
 // An update is held back (buffered) if its stripe is in the locked chunk, or if its own entry is
@@ -69,18 +99,22 @@ struct Scratch {           // device pointers carved out of the caller's scratch
 struct RecoveryView {
     uint32_t active, server, next, locked;
     uint32_t stripes_per_chunk;
+    Divider dspc;          // by stripes_per_chunk
 };
-__host__ __device__ __forceinline__ bool held_back(const RecoveryView &r, uint32_t x, uint32_t k, uint32_t S)
+__host__ __device__ __forceinline__ bool held_back(const RecoveryView &r, uint32_t x, const Divider &dk, const Divider &dS)
 {
     if (!r.active) return false;
-    const uint32_t g = x / k, j = x - g * k;
-    const uint32_t p = g % S;
+    const uint32_t k = dk.d, S = dS.d;
+    const uint32_t g = dk.div(x), j = x - g * k;
+    const uint32_t p = dS.mod(g);
     uint32_t lost = k;                                // unit of stripe g on the failed server: k = its parity
     if (p != r.server) {
-        lost = (r.server + S - (p + 1u) % S) % S;     // (g+1+lost) mod S == server
+        const uint32_t q = p + 1u == S ? 0u : p + 1u; // (g+1) mod S
+        lost = r.server + S - q;                      // in [1, 2S): (g+1+lost) mod S == server
+        if (lost >= S) lost -= S;
         if (lost >= k) return false;                  // the stripe has nothing on the failed server
     }
-    const uint32_t c = g / r.stripes_per_chunk;
+    const uint32_t c = r.dspc.div(g);
     if (c < r.next) return false;                     // already rebuilt
     if (c == r.next && r.locked) return true;         // being rebuilt right now
     return lost == j;                                 // not rebuilt yet: only the lost entry itself waits
@@ -94,12 +128,13 @@ struct Geometry {
     float lr, eps;
     float mu;              // momentum coefficient (momentum SGD only)
     uint32_t mode;         // optimizer + 2 * combine: which update rule the kernels are instantiated for
+    Divider dk, dS;        // by k and by S
 };
 
 // ---- launchers (each checks nothing: the API layer validates shapes before calling) -------------
 void launch_reset(const Scratch &s, uint32_t S, uint32_t n, bool clear_sticky, hipStream_t st);
 void launch_sort(const Scratch &s, const Geometry &g, const RecoveryView &rv, const uint64_t *keys, uint32_t n,
-                 int key_bits, uint32_t key_div, bool count_servers, uint32_t **sorted_keys,
+                 int key_bits, bool by_stripe, bool count_servers, uint32_t **sorted_keys,
                  uint32_t **sorted_vals, hipStream_t st);
 void launch_hold_back(const Scratch &s, const Geometry &g, const RecoveryView &rv, const uint64_t *keys,
                       const float *grads, uint32_t n, unsigned long long *buf_keys, float *buf_grads,

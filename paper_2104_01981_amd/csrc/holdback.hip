@@ -27,8 +27,8 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t *s_w)
 }
 
 // pass 1: how many items of each tile are held back
-__global__ __launch_bounds__(kHoldThreads) void hold_count_kernel(const uint64_t *keys, uint32_t n, uint32_t rows, uint32_t k,
-                                                                  uint32_t S, RecoveryView rv, uint32_t *tile_count)
+__global__ __launch_bounds__(kHoldThreads) void hold_count_kernel(const uint64_t *keys, uint32_t n, uint32_t rows, Divider dk,
+                                                                  Divider dS, RecoveryView rv, uint32_t *tile_count)
 {
     __shared__ uint32_t s_w[kHoldThreads / kWave];
     uint32_t c = 0;
@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kHoldThreads) void hold_count_kernel(const uint64_t
         const uint32_t i = base + r * kHoldThreads + threadIdx.x;
         if (i < n) {
             const uint64_t x = keys[i];
-            if (x < (uint64_t)rows && held_back(rv, (uint32_t)x, k, S)) ++c;
+            if (x < (uint64_t)rows && held_back(rv, (uint32_t)x, dk, dS)) ++c;
         }
     }
     const uint32_t t = block_sum(c, s_w);
@@ -86,9 +86,9 @@ __global__ __launch_bounds__(1024) void hold_scan_kernel(uint32_t *tile_count, u
 }
 
 // pass 3: position of every held-back item in the buffer (arrival order), its key, and the copy of
-// its gradient row (one wave per held-back item of the tile, 16 bytes per lane and step)
+// its gradient row (eight held-back items of the tile per wave and step, 16 bytes per lane)
 __global__ __launch_bounds__(kHoldThreads) void hold_scatter_kernel(const uint64_t *keys, const float *grads, uint32_t n,
-                                                                    uint32_t rows, uint32_t D, uint32_t k, uint32_t S,
+                                                                    uint32_t rows, uint32_t D, Divider dk, Divider dS,
                                                                     RecoveryView rv, const uint32_t *tile_offset,
                                                                     Header *hdr, unsigned long long *buf_keys,
                                                                     float *buf_grads)
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(kHoldThreads) void hold_scatter_kernel(const uint64
         held[r] = false;
         if (i < n) {
             const uint64_t x = keys[i];
-            held[r] = x < (uint64_t)rows && held_back(rv, (uint32_t)x, k, S);
+            held[r] = x < (uint64_t)rows && held_back(rv, (uint32_t)x, dk, dS);
         }
         const unsigned long long m = __ballot(held[r]);
         below[r] = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
@@ -126,16 +126,26 @@ __global__ __launch_bounds__(kHoldThreads) void hold_scatter_kernel(const uint64
     }
     __syncthreads();
     const uint32_t first = hdr->buf_count + tile_offset[blockIdx.x];
-    for (uint32_t t = wave; t < total; t += kHoldThreads / kWave) {
-        const uint32_t i = s_src[t];
-        const size_t dst = (size_t)first + t;
-        if (lane == 0) buf_keys[dst] = keys[i];
-        const rsrc_t src = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(grads + (size_t)i * D), 0, (int)(D * 4u), 0x00020000);
-        const rsrc_t out = __builtin_amdgcn_make_buffer_rsrc(buf_grads + dst * D, 0, (int)(D * 4u), 0x00020000);
+    // row copies: U rows in flight per wave (one at a time the copy ran at 2 TB/s)
+    constexpr uint32_t U = 8, W = kHoldThreads / kWave;
+    for (uint32_t t0 = wave * U; t0 < total; t0 += W * U) {
         for (uint32_t off = lane * 16u; off < D * 4u; off += kWave * 16u) {
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(src, (int)off, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b128(v, out, (int)off, 0, 0);
+            u32x4 v[U];
+#pragma unroll
+            for (uint32_t u = 0; u < U; ++u) {
+                const uint32_t i = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_src[min(t0 + u, total - 1)]);
+                const rsrc_t src = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(grads + (size_t)i * D), 0, (int)(D * 4u), 0x00020000);
+                v[u] = __builtin_amdgcn_raw_buffer_load_b128(src, (int)off, 0, 2);
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < U; ++u) {
+                if (t0 + u < total) {
+                    const rsrc_t out = __builtin_amdgcn_make_buffer_rsrc(buf_grads + ((size_t)first + t0 + u) * D, 0, (int)(D * 4u), 0x00020000);
+                    __builtin_amdgcn_raw_buffer_store_b128(v[u], out, (int)off, 0, 0);
+                }
+            }
         }
+        if (lane < U && t0 + lane < total) buf_keys[(size_t)first + t0 + lane] = keys[s_src[t0 + lane]];
     }
 }
 
@@ -150,9 +160,9 @@ void launch_hold_back(const Scratch &s, const Geometry &g, const RecoveryView &r
 {
     const uint32_t ntiles = (n + kHoldTile - 1) / kHoldTile;
     uint32_t *tile_count = s.long_slot;            // free until the chain kernels run
-    hipLaunchKernelGGL(hold_count_kernel, dim3(ntiles), dim3(kHoldThreads), 0, st, keys, n, g.rows, g.k, g.S, rv, tile_count);
+    hipLaunchKernelGGL(hold_count_kernel, dim3(ntiles), dim3(kHoldThreads), 0, st, keys, n, g.rows, g.dk, g.dS, rv, tile_count);
     hipLaunchKernelGGL(hold_scan_kernel, dim3(1), dim3(1024), 0, st, tile_count, ntiles, s.hdr, n, buf_cap);
-    hipLaunchKernelGGL(hold_scatter_kernel, dim3(ntiles), dim3(kHoldThreads), 0, st, keys, grads, n, g.rows, g.D, g.k, g.S,
+    hipLaunchKernelGGL(hold_scatter_kernel, dim3(ntiles), dim3(kHoldThreads), 0, st, keys, grads, n, g.rows, g.D, g.dk, g.dS,
                        rv, tile_count, s.hdr, buf_keys, buf_grads);
     hipLaunchKernelGGL(hold_commit_kernel, dim3(1), dim3(64), 0, st, s.hdr);
 }

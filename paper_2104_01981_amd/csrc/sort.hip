@@ -91,30 +91,31 @@ __device__ __forceinline__ uint32_t tile_of_block(uint32_t b, uint32_t nblocks)
 
 // Sort key of one caller key in the first pass, the same in the histogram and in the scatter:
 // out-of-range keys keep their low bits (the batch is rejected anyway), held-back items get `rows`.
-__device__ __forceinline__ uint32_t first_pass_key(uint64_t k64, uint32_t rows, uint32_t k, uint32_t S_place,
-                                                   const RecoveryView &rv, uint32_t key_div, bool &bad, bool &held)
+__device__ __forceinline__ uint32_t first_pass_key(uint64_t k64, uint32_t rows, const Divider &dk, const Divider &dS,
+                                                   const RecoveryView &rv, bool by_stripe, bool &bad, bool &held)
 {
     const uint32_t key = (uint32_t)k64;
     bad = k64 >= (uint64_t)rows;
-    held = !bad && held_back(rv, key, k, S_place);
+    held = !bad && held_back(rv, key, dk, dS);
     if (held) return rows;
-    return key_div > 1u ? key / key_div : key;
+    return by_stripe ? dk.div(key) : key;
 }
 
 // ---- histogram ---------------------------------------------------------------------------------
-// FIRST: keys are the caller's u64 row ids; also range check + load accounting.  key_div > 1 groups by
-// row id / key_div instead (by stripe, for the parity half of gradient propagation).
+// FIRST: keys are the caller's u64 row ids; also range check + load accounting (count != 0).  by_stripe
+// groups by row id / k instead (for the parity half of gradient propagation).
 template <bool FIRST>
 __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
     const void *keys_in, uint32_t n, uint32_t nblocks, int shift, int bits, uint32_t *block_hist,
-    Header *hdr, unsigned long long *cnt, uint32_t rows, uint32_t k, uint32_t S, uint32_t S_place, RecoveryView rv,
-    uint32_t key_div)
+    Header *hdr, unsigned long long *cnt, uint32_t rows, Divider dk, Divider dS, uint32_t count, RecoveryView rv,
+    uint32_t by_stripe)
 {
     __shared__ uint32_t s_hist[kMaxBins];
     __shared__ uint32_t s_cnt[2 * 1024];
     __shared__ uint32_t s_bad;
     const uint32_t tid = threadIdx.x;
     const uint32_t bins = 1u << bits, mask = bins - 1;
+    const uint32_t S = count ? dS.d : 0u;             // 0: the caller counts per distinct row later
     for (uint32_t i = tid; i < bins; i += kSortThreads) s_hist[i] = 0;
     if (FIRST) {
         for (uint32_t i = tid; i < 2 * S; i += kSortThreads) s_cnt[i] = 0;
@@ -132,12 +133,12 @@ __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
             if (FIRST) {
                 const uint64_t k64 = ((const uint64_t *)keys_in)[i];
                 bool oob, held;                                   // held back: sorts behind every row, not applied
-                key = first_pass_key(k64, rows, k, S_place, rv, key_div, oob, held);
+                key = first_pass_key(k64, rows, dk, dS, rv, by_stripe != 0, oob, held);
                 bad |= oob;
-                if (!oob && !held && S) {                         // S == 0: the caller counts per distinct row later
-                    const uint32_t x = (uint32_t)k64, g = x / k, j = x - g * k;
-                    atomicAdd(&s_cnt[(g + 1 + j) % S], 1u);       // server of the entry
-                    atomicAdd(&s_cnt[S + g % S], 1u);             // server of its parity
+                if (!oob && !held && S) {
+                    const uint32_t x = (uint32_t)k64, g = dk.div(x), j = x - g * dk.d;
+                    atomicAdd(&s_cnt[dS.mod(g + 1 + j)], 1u);     // server of the entry
+                    atomicAdd(&s_cnt[S + dS.mod(g)], 1u);         // server of its parity
                 }
             } else {
                 key = ((const uint32_t *)keys_in)[i];
@@ -184,7 +185,7 @@ template <bool FIRST>
 __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_kernel(
     const void *keys_in, const uint32_t *vals_in, uint32_t *keys_out, uint32_t *vals_out,
     const uint32_t *block_hist, const uint32_t *bin_total, uint32_t n, uint32_t nblocks, int shift, int bits,
-    uint32_t rows, uint32_t k, uint32_t S_place, RecoveryView rv, uint32_t key_div)
+    uint32_t rows, Divider dk, Divider dS, RecoveryView rv, uint32_t by_stripe)
 {
     __shared__ uint32_t s_keys[kSortTile];
     __shared__ uint32_t s_vals[kSortTile];
@@ -208,7 +209,7 @@ __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_ke
         if (i < n) {
             if (FIRST) {
                 bool oob, held;
-                key[r] = first_pass_key(((const uint64_t *)keys_in)[i], rows, k, S_place, rv, key_div, oob, held);
+                key[r] = first_pass_key(((const uint64_t *)keys_in)[i], rows, dk, dS, rv, by_stripe != 0, oob, held);
                 val[r] = i;
             } else {
                 key[r] = ((const uint32_t *)keys_in)[i];
@@ -299,9 +300,10 @@ void launch_clear_status(const Scratch &s, hipStream_t st)
 }
 
 void launch_sort(const Scratch &s, const Geometry &g, const RecoveryView &rv, const uint64_t *keys, uint32_t n,
-                 int key_bits, uint32_t key_div, bool count_servers, uint32_t **sorted_keys,
+                 int key_bits, bool by_stripe, bool count_servers, uint32_t **sorted_keys,
                  uint32_t **sorted_vals, hipStream_t st)
 {
+    const uint32_t count = (count_servers && !(g.mode & 2u)) ? 1u : 0u, bs = by_stripe ? 1u : 0u;
     const uint32_t nblocks = (n + kSortTile - 1) / kSortTile;
     int passes = (key_bits + kMaxRadixBits - 1) / kMaxRadixBits;
     if (passes < 1) passes = 1;
@@ -315,22 +317,22 @@ void launch_sort(const Scratch &s, const Geometry &g, const RecoveryView &rv, co
         if (p == 0) {
             hipLaunchKernelGGL(sort_hist_kernel<true>, dim3(nblocks), dim3(kSortThreads), 0, st,
                                (const void *)keys, n, nblocks, shift, bits, s.block_hist, s.hdr, s.cnt,
-                               g.rows, g.k, (!count_servers || (g.mode & 2u)) ? 0u : g.S, g.S, rv, key_div);
+                               g.rows, g.dk, g.dS, count, rv, bs);
             hipLaunchKernelGGL(sort_scan_kernel, dim3(bins), dim3(kSortThreads), 0, st, s.block_hist,
                                s.bin_total, nblocks);
             hipLaunchKernelGGL(sort_scatter_kernel<true>, dim3(nblocks), dim3(kSortThreads), 0, st,
                                (const void *)keys, (const uint32_t *)nullptr, s.keys[0], s.vals[0],
-                               s.block_hist, s.bin_total, n, nblocks, shift, bits, g.rows, g.k, g.S, rv, key_div);
+                               s.block_hist, s.bin_total, n, nblocks, shift, bits, g.rows, g.dk, g.dS, rv, bs);
             cur = 0;
         } else {
             hipLaunchKernelGGL(sort_hist_kernel<false>, dim3(nblocks), dim3(kSortThreads), 0, st,
                                (const void *)s.keys[cur], n, nblocks, shift, bits, s.block_hist, s.hdr,
-                               s.cnt, g.rows, g.k, g.S, g.S, rv, 1u);
+                               s.cnt, g.rows, g.dk, g.dS, 0u, rv, 0u);
             hipLaunchKernelGGL(sort_scan_kernel, dim3(bins), dim3(kSortThreads), 0, st, s.block_hist,
                                s.bin_total, nblocks);
             hipLaunchKernelGGL(sort_scatter_kernel<false>, dim3(nblocks), dim3(kSortThreads), 0, st,
                                (const void *)s.keys[cur], s.vals[cur], s.keys[cur ^ 1], s.vals[cur ^ 1],
-                               s.block_hist, s.bin_total, n, nblocks, shift, bits, g.rows, g.k, g.S, rv, 1u);
+                               s.block_hist, s.bin_total, n, nblocks, shift, bits, g.rows, g.dk, g.dS, rv, 0u);
             cur ^= 1;
         }
         shift += bits;

@@ -939,7 +939,7 @@ __global__ __launch_bounds__(256) void recovery_read_kernel(ReadArgs a)
             }
         }
         uint32_t lo = a.m;                        // first waiting update of x, if it can have any
-        if (a.m && held_back(a.rv, x, k, S)) {
+        if (a.m && held_back(a.rv, x, a.geo.dk, a.geo.dS)) {
             uint32_t l = 0, h = a.m;
             while (l < h) {
                 const uint32_t mid = l + (h - l) / 2;
