@@ -27,9 +27,9 @@ LONG_RUN = 1024          # ECRM_LONG_RUN of include/ecrm.h: longer runs leave th
 # HBM bytes per launch of the apply kernel on the default workload, from rocprofv3 FETCH_SIZE and
 # WRITE_SIZE scaled by a plain copy of known size (profiles/update_path_hbm_scale_hbm_traffic.txt).
 # Reported only while the kernel's sources are the ones the counters were taken on.
-TRAFFIC_BYTES_PER_LAUNCH = 38002507905
+TRAFFIC_BYTES_PER_LAUNCH = 38002369612
 TRAFFIC_SOURCES = ["paper_2104_01981_amd/csrc/update.hip", "paper_2104_01981_amd/csrc/ecrm_internal.h"]
-TRAFFIC_SOURCES_SHA256 = "f5ef1b43ee1b061eddcbb8c320cebb3ed5f7ecadaa942c9265d9e282aff20ad1"
+TRAFFIC_SOURCES_SHA256 = "cc90ca6fa60044009fa77d285bc8052bcd21220924c69f932d29d99583528603"
 
 
 def measured_traffic(workload, scale_shift, variant=""):
