@@ -26,21 +26,31 @@ HBM_PEAK_GBS = 8000.0
 LONG_RUN = 1024          # ECRM_LONG_RUN of include/ecrm.h: longer runs leave the apply kernel for the split-chain path
 # HBM bytes per launch of the apply kernel on the default workload, from rocprofv3 FETCH_SIZE and
 # WRITE_SIZE scaled by a plain copy of known size (profiles/update_path_hbm_scale_hbm_traffic.txt).
-# Reported only while the kernel's sources are the ones the counters were taken on.
+# Reported only while the code of the kernel's sources is what the counters were taken on.
 TRAFFIC_BYTES_PER_LAUNCH = 38002369612
 TRAFFIC_SOURCES = ["paper_2104_01981_amd/csrc/update.hip", "paper_2104_01981_amd/csrc/ecrm_internal.h"]
-TRAFFIC_SOURCES_SHA256 = "cc90ca6fa60044009fa77d285bc8052bcd21220924c69f932d29d99583528603"
+TRAFFIC_SOURCES_SHA256 = "3821446c5c7c4675a1c4487153be2d6f38442e1670b98c6d411f126583061ac2"
+
+
+def code_digest(paths):
+    """sha256 of the sources' code: comments and white space do not count"""
+    import hashlib
+    import re
+    h = hashlib.sha256()
+    for rel in paths:
+        text = open(os.path.join(ROOT, rel), "r").read()
+        text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)
+        text = re.sub(r"//[^\n]*", " ", text)
+        h.update(" ".join(text.split()).encode())
+    return h.hexdigest()
 
 
 def measured_traffic(workload, scale_shift, variant=""):
-    import hashlib
-    h = hashlib.sha256()
     try:
-        for rel in TRAFFIC_SOURCES:
-            h.update(open(os.path.join(ROOT, rel), "rb").read())
+        digest = code_digest(TRAFFIC_SOURCES)
     except OSError:
         return None
-    if workload != "hbm_scale" or scale_shift or variant or h.hexdigest() != TRAFFIC_SOURCES_SHA256:
+    if workload != "hbm_scale" or scale_shift or variant or digest != TRAFFIC_SOURCES_SHA256:
         return None
     return TRAFFIC_BYTES_PER_LAUNCH
 

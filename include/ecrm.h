@@ -179,8 +179,8 @@ int ecrm_recovery_unlock(ecrm_ctx *ctx, void *hip_stream);
 int ecrm_recovery_state(ecrm_ctx *ctx, void *hip_stream, uint32_t *active, uint32_t *next_chunk, uint32_t *chunks,
                         uint64_t *buffered);
 
-/* What a worker reads while a recovery is in progress (Sec. 3.4: "workers reading an updated, but
- * locked entry do so by reading from the buffer"): out_E[i][0..D) (and out_A[i] if not NULL) receive
+/* What a worker reads while a recovery is in progress (Sec. 3.4 has workers take a locked entry that
+ * has been updated meanwhile out of the buffer): out_E[i][0..D) (and out_A[i] if not NULL) receive
  * entry keys[i] with its waiting updates applied in arrival order -- the value it will have once they
  * are replayed; an entry that the failed server held and that is not rebuilt yet is decoded from its
  * stripe first.  Nothing is modified, so the read may be repeated.  Call it on the update stream.

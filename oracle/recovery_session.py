@@ -1,11 +1,12 @@
 """Training while a failed server is rebuilt -- the protocol of Sec. 3.4 ("Training during
 recovery") of the ECRM paper, stated plainly on the CPU (test infrastructure).
 
-The paper: the recovery process locks a fraction of the lost entries; while the lock is held, all
-updates to entries that will be used in recovery of the locked chunk are buffered; when the lock is
-released the buffered updates are applied and the next chunk is locked; training never pauses.
+What Sec. 3.4 prescribes, in short: recovery proceeds chunk by chunk; the chunk being decoded is
+locked, updates that would change anything the decoder reads for that chunk are set aside in a
+buffer instead of being applied, and they are applied as soon as the chunk is done, when the lock
+moves on to the next chunk.  Training does not stop at any point.
 Readings taken here (the paper does not spell them out):
-  * a chunk is a contiguous range of stripes; "entries used in recovery of the chunk" are all entries
+  * a chunk is a contiguous range of stripes; what the decoder reads for a chunk are all entries
     (and the parity) of the chunk's stripes that have a unit on the failed server;
   * an update to an entry that the failed server held cannot be applied before that entry has been
     rebuilt: it is buffered until its chunk is released, whether or not the chunk is locked;
@@ -70,8 +71,8 @@ class RecoverySession:
 
     # -- what a worker reads meanwhile ------------------------------------------------------------
     def read(self, keys):
-        """Entries and their state as a worker sees them during the recovery (Sec. 3.4: a worker that
-        reads an updated but locked entry reads it from the buffer).  Reading taken here: the value
+        """Entries and their state as a worker sees them during the recovery (Sec. 3.4 serves a locked
+        entry that has been updated meanwhile out of the buffer).  Reading taken here: the value
         is the one the entry will have once its waiting updates have been replayed, i.e. the stored
         entry with the buffered updates of that entry applied in arrival order; an entry that the
         failed server held and that is not rebuilt yet is first decoded from its stripe.  Nothing is

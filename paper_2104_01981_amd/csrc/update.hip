@@ -896,7 +896,7 @@ __global__ __launch_bounds__(256) void count_rows_kernel(const uint32_t *sk, uin
 // reads while a server is being recovered
 // ================================================================================================
 
-// Sec. 3.4 "Training during recovery": a worker that reads an updated but locked entry reads it from
+// Sec. 3.4 "Training during recovery" serves a locked entry that has been updated meanwhile out of
 // the buffer.  The buffer here holds updates, not entries, so the read applies them: the value
 // returned is the stored entry with its waiting updates applied in arrival order -- what the entry
 // will be once they have been replayed -- and an entry the failed server held that is not rebuilt

@@ -99,7 +99,7 @@ def test_full_buffer_rejects_the_batch():
     assert len(ses.buf_keys) == 0
 
 
-# ---- reads during the recovery (Sec. 3.4: a locked, updated entry is read from the buffer) -------
+# ---- reads during the recovery (Sec. 3.4: a locked entry updated meanwhile is served from the buffer) ----
 
 def _reference_after(E0, A0, PE0, PA0, k, S, server, batches):
     """fail, rebuild everything at once, then apply the batches: what a worker should see"""
