@@ -153,8 +153,8 @@ def main():
     ctx = Ecrm(R, D, k, S, si.DEFAULT_LR, si.DEFAULT_EPS, per, optimizer=1 if args.optimizer == "momentum" else 0,
                momentum=0.9 if args.optimizer == "momentum" else 0.0, combine=1 if args.combine else 0, propagation=prop)
     # One arena for everything that stays resident (tables, scratch, all batches), carved at 2 MiB.
-    # Order matters on this device: tables that are swept together must start >= 32 GiB apart, so
-    # batches are placed between them.
+    # Order matters on this device (see the list of layouts below): batches are placed between the
+    # tables.
     ALIGN = 2 << 20
     sizes = {"E": R * D * 4, "A": R * D * 4, "PE": R // k * D * 4, "PA": R // k * D * 4, "ld": S * 8, "lp": S * 8,
              "scratch": ctx.scratch_bytes()}
