@@ -103,7 +103,7 @@ def main():
                     help="diagnostic: after the timed region, run the steps again one by one and log each one's phases")
     args = ap.parse_args()
     if args.gpus != 1:
-        log("bench.py: this build runs on ONE GPU (all servers' shards in one HBM); "
+        log("bench.py: this library runs on ONE GPU (all servers' shards in one HBM); "
             "--gpus must be 1, no multi-GPU figure exists.")
         sys.exit(2)
 
@@ -166,8 +166,8 @@ def main():
     # starts in physical memory (measured: the first layout runs at 0.75 of the HBM peak with 0-48 GiB
     # of padding in front of it, at 0.68 with 56 GiB, at 0.75 again with 64 GiB; with the parity
     # tables moved from 64 to 80 GiB behind E it runs at 0.63).  All layouts below measured 0.75 on
-    # an ordinary box; they differ in both respects, so that a box on which one of them lands badly
-    # has others to offer.
+    # an ordinary machine; they differ in both respects, so that a machine on which one of them lands
+    # badly has others to offer.
     GEOMETRIES = ["E,g0,g1,A,g2,g3,PE,PA,scratch,keys,g*",
                   "pad16,E,g0,g1,A,g2,g3,PE,PA,scratch,keys,g*",
                   "E,g0,g1,g2,g3,A,g4,g5,g6,g7,PE,PA,scratch,keys,g*",

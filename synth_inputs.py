@@ -223,7 +223,7 @@ def mixed_keys(seed, start, count, R, n_ranks, theta=0.99):
 
 
 # ----------------------------------------------------------------------------------------------
-# the five workloads (sizes, seeds and skew from the task's configuration list; D, k, S from the
+# the five workloads (sizes, seeds and skew are this repository's own choice; D, k, S from the
 # paper's evaluation setup: 128 features per entry, k = 4, five servers)
 # ----------------------------------------------------------------------------------------------
 
