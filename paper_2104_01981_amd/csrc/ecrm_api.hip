@@ -15,7 +15,8 @@ struct ecrm_ctx {
     uint32_t max_batch, max_slots, max_pieces, max_blocks;
     size_t scratch_bytes;
     size_t off_cnt, off_keys[2], off_vals[2], off_hist, off_bintotal, off_long_slot, off_long_meta,
-        off_piece_slot, off_partial, off_long_res;
+        off_piece_slot, off_partial, off_partial2, off_long_res;
+    bool has_partial2;
     // bound state
     bool bound, need_init;
     float *E, *A, *PE, *PA;
@@ -69,6 +70,8 @@ static void layout(ecrm_ctx *c)
     c->off_long_meta = take((size_t)5 * c->max_slots * 4);
     c->off_piece_slot = take((size_t)c->max_pieces * 4);
     c->off_partial = take((size_t)c->max_pieces * D * sizeof(double));
+    c->has_partial2 = c->cfg.optimizer == ECRM_OPT_MOMENTUM && !c->cfg.combine;
+    c->off_partial2 = take(c->has_partial2 ? (size_t)c->max_pieces * D * sizeof(double) : 0);
     c->off_long_res = take((size_t)c->max_slots * 2 * D * sizeof(double));
     c->scratch_bytes = off;
 }
@@ -186,6 +189,7 @@ int ecrm_bind(ecrm_ctx *c, float *E, float *A, float *PE, float *PA, uint64_t *l
     c->s.long_base = meta + (size_t)4 * c->max_slots;
     c->s.piece_slot = (uint32_t *)(b + c->off_piece_slot);
     c->s.partial = (double *)(b + c->off_partial);
+    c->s.partial2 = c->has_partial2 ? (double *)(b + c->off_partial2) : nullptr;
     c->s.long_res = (double *)(b + c->off_long_res);
 
     c->E = E; c->A = A; c->PE = PE; c->PA = PA;

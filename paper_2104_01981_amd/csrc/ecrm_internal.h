@@ -59,6 +59,7 @@ struct Scratch {           // device pointers carved out of the caller's scratch
     uint32_t *long_head, *long_len, *long_piece, *long_count, *long_base;   // [max_slots]
     uint32_t *piece_slot;          // [max_pieces]
     double *partial;               // [max_pieces][D]
+    double *partial2;              // [max_pieces][D], momentum SGD only (else null)
     double *long_res;              // [max_slots][2][D]: sum of steps, final accumulator
 };
 

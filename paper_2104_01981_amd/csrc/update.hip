@@ -235,6 +235,10 @@ __global__ __launch_bounds__(256) void long_plan_kernel(const uint32_t *sk, uint
 
 // Phase 1 (STEPS == false): partial[piece] = the piece's summary started from zero (Adagrad: sum of
 //                           g^2; momentum: the velocity it builds; combined rules: sum of g).
+//                           Momentum also gets partial2[piece] = the sum of the velocities the piece
+//                           goes through when started from zero: its rule is linear, so the steps of
+//                           a piece started from velocity v are lr * (c * v + that sum) with
+//                           c = mu + mu^2 + ... + mu^len, and the gradients need no second read.
 // Phase 3 (STEPS == true):  partial[piece] holds the piece's starting state on entry and the sum of
 //                           its steps on exit (sequential rules only).
 // One wave per piece; the item indices of 64 positions are fetched with one coalesced load and
@@ -244,8 +248,9 @@ __global__ __launch_bounds__(256) void long_piece_kernel(const uint32_t *si, con
                                                          const uint32_t *long_head, const uint32_t *long_len,
                                                          const uint32_t *long_piece, const uint32_t *long_base,
                                                          const uint32_t *piece_slot, double *partial,
-                                                         uint32_t max_pieces, Geometry geo)
+                                                         double *partial2, uint32_t max_pieces, Geometry geo)
 {
+    constexpr bool kVelSum = !STEPS && MODE == kMomentumSeq;
     if (hdr->batch_bad) return;
     const uint32_t np = min(hdr->n_pieces, max_pieces);
     const uint32_t D = geo.D, lane = lane_id();
@@ -260,10 +265,10 @@ __global__ __launch_bounds__(256) void long_piece_kernel(const uint32_t *si, con
         for (uint32_t cb = 0; cb < geo.ncb; ++cb) {
             const uint32_t col0 = cb * NC * 128u;
             const rsrc_t part = row_f64(partial, pc, D, col0);
-            D2 G[NC], acc[NC];
+            D2 G[NC], acc[NC], vs[NC];
 #pragma unroll
             for (int i = 0; i < NC; ++i) {
-                acc[i] = D2{0, 0};
+                acc[i] = vs[i] = D2{0, 0};
                 G[i] = STEPS ? ldd2(part, i) : D2{0, 0};
             }
             uint32_t widx = start + lane < end ? si[start + lane] : 0u;
@@ -289,6 +294,10 @@ __global__ __launch_bounds__(256) void long_piece_kernel(const uint32_t *si, con
                             for (int i = 0; i < NC; ++i) {
                                 if (STEPS) item2<MODE>(G[i], acc[i], g[u][i], rp);
                                 else summary2<MODE>(acc[i], g[u][i], rp);
+                                if (kVelSum) {
+                                    vs[i].x += acc[i].x;
+                                    vs[i].y += acc[i].y;
+                                }
                             }
                         }
                     }
@@ -296,6 +305,11 @@ __global__ __launch_bounds__(256) void long_piece_kernel(const uint32_t *si, con
             }
 #pragma unroll
             for (int i = 0; i < NC; ++i) std2(part, i, acc[i]);
+            if (kVelSum) {
+                const rsrc_t part2 = row_f64(partial2, pc, D, col0);
+#pragma unroll
+                for (int i = 0; i < NC; ++i) std2(part2, i, vs[i]);
+            }
         }
     }
 }
@@ -305,13 +319,15 @@ constexpr int kRowWaves = 16;      // waves that share one long row in the scan 
 // Phase 2: exclusive scan of the pieces' summaries, seeded with the stored state, so that every
 // piece knows the state it starts from: Adagrad adds the sums of squares; momentum composes
 // v -> mu^len * v + V_piece.  long_res[slot][1] receives the state after the whole run.
+// Adagrad: partial[piece] leaves as the piece's starting state (the steps need a second pass over
+// its gradients); momentum: it leaves as the sum of the piece's steps, from partial2 (see above).
 // One block of 16 waves per long row: every wave folds a contiguous range of pieces, the ranges'
 // results are exchanged through LDS, and every wave then rewrites its range with the prefixes.
 template <int NC, int MODE>
 __global__ __launch_bounds__(kRowWaves * kWave) void long_scan_kernel(
     const uint32_t *sk, const float *A, Header *hdr, const uint32_t *long_head, const uint32_t *long_count,
     const uint32_t *long_base, const uint32_t *long_len, const uint32_t *long_piece, double *partial,
-    double *long_res, uint32_t max_slots, Geometry geo)
+    const double *partial2, double *long_res, uint32_t max_slots, Geometry geo)
 {
     __shared__ double s_fold[kRowWaves][NC][2][kWave];
     if (hdr->batch_bad) return;
@@ -328,6 +344,9 @@ __global__ __launch_bounds__(kRowWaves * kWave) void long_scan_kernel(
         const double mu = (double)geo.mu;
         const double decay_full = MODE == kMomentumSeq ? pow(mu, (double)C) : 1.0;
         const double decay_last = MODE == kMomentumSeq ? pow(mu, (double)(L - (P - 1) * C)) : 1.0;
+        // mu + mu^2 + ... + mu^len for a full piece and for the last one
+        const double geo_full = mu * (1.0 - decay_full) / (1.0 - mu), geo_last = mu * (1.0 - decay_last) / (1.0 - mu);
+        const double lr = (double)geo.lr;
         for (uint32_t cb = 0; cb < geo.ncb; ++cb) {
             const uint32_t col0 = cb * NC * 128u;
             // (a) fold of this wave's range, started from zero
@@ -395,21 +414,32 @@ __global__ __launch_bounds__(kRowWaves * kWave) void long_scan_kernel(
             }
             // (c) rewrite this wave's range with the prefixes
             for (uint32_t j0 = j_lo; j0 < j_hi; j0 += U) {
-                D2 t[U][NC];
+                D2 t[U][NC], t2[U][NC];
 #pragma unroll
                 for (uint32_t u = 0; u < U; ++u) {
                     const rsrc_t r = row_f64(partial, base + min(j0 + u, j_hi - 1), D, col0);
 #pragma unroll
                     for (int i = 0; i < NC; ++i) t[u][i] = ldd2(r, i);
+                    if (MODE == kMomentumSeq) {
+                        const rsrc_t r2 = row_f64(partial2, base + min(j0 + u, j_hi - 1), D, col0);
+#pragma unroll
+                        for (int i = 0; i < NC; ++i) t2[u][i] = ldd2(r2, i);
+                    }
                 }
 #pragma unroll
                 for (uint32_t u = 0; u < U; ++u) {
                     if (j0 + u < j_hi) {
                         const rsrc_t r = row_f64(partial, base + j0 + u, D, col0);
-                        const double dec = j0 + u + 1 == P ? decay_last : decay_full;
+                        const bool is_last = j0 + u + 1 == P;
+                        const double dec = is_last ? decay_last : decay_full;
 #pragma unroll
                         for (int i = 0; i < NC; ++i) {
-                            std2(r, i, G[i]);
+                            if (MODE == kMomentumSeq) {          // the piece's steps, from its starting velocity
+                                const double c = is_last ? geo_last : geo_full;
+                                std2(r, i, D2{lr * fma(c, G[i].x, t2[u][i].x), lr * fma(c, G[i].y, t2[u][i].y)});
+                            } else {
+                                std2(r, i, G[i]);
+                            }
                             if (MODE == kMomentumSeq) {
                                 G[i].x = fma(dec, G[i].x, t[u][i].x);
                                 G[i].y = fma(dec, G[i].y, t[u][i].y);
@@ -1037,12 +1067,14 @@ static void chains_for(const Scratch &s, const Geometry &g, const float *A, cons
     hipLaunchKernelGGL(long_plan_kernel, grid, block, 0, st, sk, n, s.hdr, s.long_head, s.long_len, s.long_piece,
                        s.long_count, s.long_base, s.piece_slot, max_slots, max_pieces);
     hipLaunchKernelGGL((long_piece_kernel<NC, false, MODE>), dim3(grid_p1), block, 0, st, si, grads, s.hdr, s.long_head,
-                       s.long_len, s.long_piece, s.long_base, s.piece_slot, s.partial, max_pieces, g);
+                       s.long_len, s.long_piece, s.long_base, s.piece_slot, s.partial, s.partial2, max_pieces, g);
     if (!Rule<MODE>::combine) {
         hipLaunchKernelGGL((long_scan_kernel<NC, MODE>), dim3(cus * 2), dim3(kRowWaves * kWave), 0, st, sk, A, s.hdr, s.long_head, s.long_count,
-                           s.long_base, s.long_len, s.long_piece, s.partial, s.long_res, max_slots, g);
-        hipLaunchKernelGGL((long_piece_kernel<NC, true, MODE>), dim3(grid_p3), block, 0, st, si, grads, s.hdr,
-                           s.long_head, s.long_len, s.long_piece, s.long_base, s.piece_slot, s.partial, max_pieces, g);
+                           s.long_base, s.long_len, s.long_piece, s.partial, s.partial2, s.long_res, max_slots, g);
+        if (MODE != kMomentumSeq)        // momentum's steps came out of the scan: no second pass over the gradients
+            hipLaunchKernelGGL((long_piece_kernel<NC, true, MODE>), dim3(grid_p3), block, 0, st, si, grads, s.hdr,
+                               s.long_head, s.long_len, s.long_piece, s.long_base, s.piece_slot, s.partial, s.partial2,
+                               max_pieces, g);
     }
     hipLaunchKernelGGL((long_reduce_kernel<NC>), dim3(cus * 2), dim3(kRowWaves * kWave), 0, st, s.hdr, s.long_count, s.long_base, s.partial,
                        s.long_res, max_slots, g);
