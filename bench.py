@@ -27,9 +27,9 @@ LONG_RUN = 1024          # ECRM_LONG_RUN of include/ecrm.h: longer runs leave th
 # HBM bytes per launch of the apply kernel on the default workload, from rocprofv3 FETCH_SIZE and
 # WRITE_SIZE scaled by a plain copy of known size (profiles/update_path_hbm_scale_hbm_traffic.txt).
 # Reported only while the code of the kernel's sources is what the counters were taken on.
-TRAFFIC_BYTES_PER_LAUNCH = 38002369612
+TRAFFIC_BYTES_PER_LAUNCH = 38002565724
 TRAFFIC_SOURCES = ["paper_2104_01981_amd/csrc/update.hip", "paper_2104_01981_amd/csrc/ecrm_internal.h"]
-TRAFFIC_SOURCES_SHA256 = "3821446c5c7c4675a1c4487153be2d6f38442e1670b98c6d411f126583061ac2"
+TRAFFIC_SOURCES_SHA256 = "92d3c3a1ac2f43a283634fb2b53dc7adb3368e5bb921c46d720ff80a187ae990"
 
 
 def code_digest(paths):
