@@ -97,7 +97,8 @@ size_t ecrm_scratch_bytes(const ecrm_ctx *ctx);
 /* Attaches caller-owned device buffers.  scratch must be 256-byte aligned and at least
  * ecrm_scratch_bytes() long; its contents are private to the library while bound.  The load
  * counters are accumulated into, never cleared.  Returns EINVAL for a NULL / misaligned table,
- * ESCRATCH for the scratch buffer. */
+ * ESCRATCH for the scratch buffer, ESTATE while a recovery is in progress (the updates waiting in its
+ * buffer would be lost), EHIP if the device cannot be queried.  Call it outside a stream capture. */
 int ecrm_bind(ecrm_ctx *ctx, float *E, float *A, float *PE, float *PA,
               uint64_t *load_data, uint64_t *load_parity, void *scratch, size_t scratch_bytes);
 
@@ -157,13 +158,16 @@ int ecrm_degraded_read(ecrm_ctx *ctx, const uint64_t *keys, uint64_t n, uint32_t
  *
  *   ecrm_recovery_begin   declares `server` lost (its rows are NOT overwritten; use ecrm_fail_server
  *                         in tests) and hands over the buffer: device memory for 2*capacity keys
- *                         (u64) and 2*capacity gradient rows, capacity <= max_batch.
+ *                         (u64) and 2*capacity gradient rows, capacity <= max_batch.  EINVAL with
+ *                         combine = 1: synchronous training takes one step per entry and training step,
+ *                         and a buffer replayed in one go would merge the waiting updates of several
+ *                         steps into one.
  *   ecrm_recovery_lock    host-side only: from now on ecrm_update buffers what touches the next chunk.
  *   ecrm_recovery_decode  enqueues the reconstruction of the locked chunk.  It may run on another
  *                         stream than the updates, provided it starts after every ecrm_update that was
  *                         enqueued BEFORE the lock has finished (an event from that stream).
  *   ecrm_recovery_unlock  call on the update stream once the decode has finished (wait for its event
- *                         first).  SYNCHRONISES the stream to learn how many updates are waiting,
+ *                         first; ESTATE if no decode was enqueued under this lock).  SYNCHRONISES the stream to learn how many updates are waiting,
  *                         releases the chunk and enqueues the replay of the buffer (what must keep
  *                         waiting goes back into the buffer).  After the last chunk the recovery ends.
  *   ecrm_recovery_state   waits for the stream; reports whether a recovery is active, the number of

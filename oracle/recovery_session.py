@@ -11,7 +11,11 @@ Readings taken here (the paper does not spell them out):
   * an update to an entry that the failed server held cannot be applied before that entry has been
     rebuilt: it is buffered until its chunk is released, whether or not the chunk is locked;
   * buffered updates are replayed in arrival order; their load is counted when they are applied;
-  * a batch whose buffered part does not fit the buffer is rejected as a whole.
+  * a batch whose buffered part does not fit the buffer is rejected as a whole;
+  * the protocol is stated for asynchronous training (one update at a time, Sec. 2.1, 3.3.2) only.
+    The synchronous variant sketched in Sec. 4.4 takes ONE step per modified entry and training step;
+    a buffer that is replayed in one go would merge the waiting updates of several steps into a single
+    step, which is not the training that would have happened without the failure.  combine=1 is refused.
 All arithmetic is the oracle's (oracle.update / oracle.update_rule / oracle.recover_range).
 """
 from __future__ import annotations
@@ -24,6 +28,8 @@ import oracle
 class RecoverySession:
     def __init__(self, E, A, PE, PA, k, S, lr, eps, server, chunks, capacity, load_data=None, load_parity=None,
                  optimizer=0, momentum=0.0, combine=0, threads=1):
+        if combine:
+            raise ValueError("recovery under load is defined for asynchronous training only (combine=0)")
         self.E, self.A, self.PE, self.PA = E, A, PE, PA
         self.k, self.S, self.lr, self.eps = k, S, lr, eps
         self.optimizer, self.momentum, self.combine, self.threads = optimizer, momentum, combine, threads

@@ -8,25 +8,38 @@
 
 using namespace ecrm;
 
+// Where everything lies inside a scratch buffer that serves batches of up to max_batch items.
+struct Layout {
+    uint32_t max_batch, max_slots, max_pieces, max_blocks;
+    size_t bytes;
+    size_t off_cnt, off_keys[2], off_vals[2], off_hist, off_bintotal, off_long_slot, off_long_meta,
+        off_piece_slot, off_partial, off_partial2, off_long_res;
+};
+
+// The caller's device arrays one update works on.
+struct Tables {
+    float *E, *A, *PE, *PA;
+    unsigned long long *load_data, *load_parity;
+};
+
 struct ecrm_ctx {
     ecrm_config cfg;
     Geometry geo;
     int key_bits;
-    uint32_t max_batch, max_slots, max_pieces, max_blocks;
-    size_t scratch_bytes;
-    size_t off_cnt, off_keys[2], off_vals[2], off_hist, off_bintotal, off_long_slot, off_long_meta,
-        off_piece_slot, off_partial, off_partial2, off_long_res;
+    Layout lay;               // of the scratch buffer the caller binds (sized by cfg.max_batch)
     bool has_partial2;
     // bound state
     bool bound, need_init;
-    float *E, *A, *PE, *PA;
-    unsigned long long *load_data, *load_parity;
+    Tables t;
     Scratch s;
+    bool have_device;         // cus, grid sizes known (ecrm_bind)
     int grid_blocks;          // 8 blocks of 256 threads per CU, for the streaming kernels
     int cus;
+    LaunchGrids lg;           // resident grids of the grid-stride kernels (filled by ecrm_bind)
     // recovery in progress (host-side state machine; the device sees it as a RecoveryView per call)
     RecoveryView rv;
     uint32_t rec_chunks;
+    bool rec_decoded;         // the locked chunk's reconstruction has been enqueued
     unsigned long long *buf_keys[2];
     float *buf_grads[2];
     uint32_t buf_cap, buf_cur;
@@ -56,24 +69,55 @@ static bool divider_ok(const Divider &v)
     return true;
 }
 
-static void layout(ecrm_ctx *c)
+static Layout make_layout(uint32_t max_batch, uint32_t D, uint32_t S, bool has_partial2)
 {
-    const size_t n = c->max_batch, D = c->geo.D;
+    Layout l;
+    l.max_batch = max_batch;
+    l.max_blocks = (max_batch + kSortTile - 1) / kSortTile;
+    l.max_slots = max_batch / kLongRun + 1;
+    l.max_pieces = max_batch / kPieceMin + l.max_slots + 1;
+    const size_t n = max_batch;
     size_t off = sizeof(Header);
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-    c->off_cnt = take(2 * (size_t)c->geo.S * sizeof(unsigned long long));
-    for (int i = 0; i < 2; ++i) c->off_keys[i] = take(n * 4);
-    for (int i = 0; i < 2; ++i) c->off_vals[i] = take(n * 4);
-    c->off_hist = take((size_t)kMaxBins * c->max_blocks * 4);
-    c->off_bintotal = take(kMaxBins * 4);
-    c->off_long_slot = take(n * 4);
-    c->off_long_meta = take((size_t)5 * c->max_slots * 4);
-    c->off_piece_slot = take((size_t)c->max_pieces * 4);
-    c->off_partial = take((size_t)c->max_pieces * D * sizeof(double));
-    c->has_partial2 = c->cfg.optimizer == ECRM_OPT_MOMENTUM && !c->cfg.combine;
-    c->off_partial2 = take(c->has_partial2 ? (size_t)c->max_pieces * D * sizeof(double) : 0);
-    c->off_long_res = take((size_t)c->max_slots * 2 * D * sizeof(double));
-    c->scratch_bytes = off;
+    l.off_cnt = take(2 * (size_t)S * sizeof(unsigned long long));
+    for (int i = 0; i < 2; ++i) l.off_keys[i] = take(n * 4);
+    for (int i = 0; i < 2; ++i) l.off_vals[i] = take(n * 4);
+    l.off_hist = take((size_t)kMaxBins * l.max_blocks * 4);
+    l.off_bintotal = take(kMaxBins * 4);
+    l.off_long_slot = take(n * 4);
+    l.off_long_meta = take((size_t)5 * l.max_slots * 4);
+    l.off_piece_slot = take((size_t)l.max_pieces * 4);
+    l.off_partial = take((size_t)l.max_pieces * D * sizeof(double));
+    l.off_partial2 = take(has_partial2 ? (size_t)l.max_pieces * D * sizeof(double) : 0);
+    l.off_long_res = take((size_t)l.max_slots * 2 * D * sizeof(double));
+    l.bytes = off;
+    return l;
+}
+
+static Scratch carve(const Layout &l, void *base, bool has_partial2)
+{
+    char *b = (char *)base;
+    Scratch s;
+    s.hdr = (Header *)b;
+    s.cnt = (unsigned long long *)(b + l.off_cnt);
+    for (int i = 0; i < 2; ++i) {
+        s.keys[i] = (uint32_t *)(b + l.off_keys[i]);
+        s.vals[i] = (uint32_t *)(b + l.off_vals[i]);
+    }
+    s.block_hist = (uint32_t *)(b + l.off_hist);
+    s.bin_total = (uint32_t *)(b + l.off_bintotal);
+    s.long_slot = (uint32_t *)(b + l.off_long_slot);
+    uint32_t *meta = (uint32_t *)(b + l.off_long_meta);
+    s.long_head = meta;
+    s.long_len = meta + (size_t)l.max_slots;
+    s.long_piece = meta + (size_t)2 * l.max_slots;
+    s.long_count = meta + (size_t)3 * l.max_slots;
+    s.long_base = meta + (size_t)4 * l.max_slots;
+    s.piece_slot = (uint32_t *)(b + l.off_piece_slot);
+    s.partial = (double *)(b + l.off_partial);
+    s.partial2 = has_partial2 ? (double *)(b + l.off_partial2) : nullptr;
+    s.long_res = (double *)(b + l.off_long_res);
+    return s;
 }
 
 extern "C" {
@@ -132,11 +176,8 @@ int ecrm_create(const ecrm_config *cfg, ecrm_ctx **out)
     }
     c->key_bits = 1;
     while (c->key_bits < 32 && (1ull << c->key_bits) < cfg->rows) ++c->key_bits;
-    c->max_batch = (uint32_t)cfg->max_batch;
-    c->max_blocks = (c->max_batch + kSortTile - 1) / kSortTile;
-    c->max_slots = c->max_batch / kLongRun + 1;
-    c->max_pieces = c->max_batch / kPieceMin + c->max_slots + 1;
-    layout(c);
+    c->has_partial2 = cfg->optimizer == ECRM_OPT_MOMENTUM && !cfg->combine;
+    c->lay = make_layout((uint32_t)cfg->max_batch, cfg->dim, cfg->servers, c->has_partial2);
     *out = c;
     return ECRM_OK;
 }
@@ -152,49 +193,42 @@ void ecrm_destroy(ecrm_ctx *c)
 
 size_t ecrm_data_bytes(const ecrm_ctx *c) { return c ? (size_t)c->cfg.rows * c->cfg.dim * 4 : 0; }
 size_t ecrm_parity_bytes(const ecrm_ctx *c) { return c ? (size_t)(c->cfg.rows / c->cfg.k) * c->cfg.dim * 4 : 0; }
-size_t ecrm_scratch_bytes(const ecrm_ctx *c) { return c ? c->scratch_bytes : 0; }
+size_t ecrm_scratch_bytes(const ecrm_ctx *c) { return c ? c->lay.bytes : 0; }
 
 static bool aligned(const void *p, size_t a) { return p && ((uintptr_t)p % a) == 0; }
+
+// Learns the device the context runs on (compute units, resident grid sizes), once.  Host-side queries
+// only; nothing is enqueued.
+static int learn_device(ecrm_ctx *c)
+{
+    if (c->have_device) return ECRM_OK;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return ECRM_EHIP;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return ECRM_EHIP;
+    LaunchGrids lg;
+    if (!query_launch_grids(c->geo, cus, &lg)) return ECRM_EHIP;
+    c->lg = lg;
+    c->cus = cus;
+    c->grid_blocks = cus * 8;     // 8 x 256 threads = the 2048 threads a CU can hold
+    c->have_device = true;
+    return ECRM_OK;
+}
 
 int ecrm_bind(ecrm_ctx *c, float *E, float *A, float *PE, float *PA, uint64_t *load_data,
               uint64_t *load_parity, void *scratch, size_t scratch_bytes)
 {
     if (!c) return ECRM_EINVAL;
+    if (c->rv.active) return ECRM_ESTATE;      // updates are waiting in the recovery buffer: binding would drop them
     if (!aligned(E, 16) || !aligned(A, 16) || !aligned(PE, 16) || !aligned(PA, 16)) return ECRM_EINVAL;
     if (!aligned(load_data, 8) || !aligned(load_parity, 8)) return ECRM_EINVAL;
-    if (!aligned(scratch, 256) || scratch_bytes < c->scratch_bytes) return ECRM_ESCRATCH;
+    if (!aligned(scratch, 256) || scratch_bytes < c->lay.bytes) return ECRM_ESCRATCH;
+    const int rc = learn_device(c);
+    if (rc != ECRM_OK) return rc;
 
-    int dev = 0, cus = 0, per_cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return ECRM_EHIP;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return ECRM_EHIP;
-    (void)per_cu;
-    c->cus = cus;
-    c->grid_blocks = cus * 8;     // 8 x 256 threads = the 2048 threads a CU can hold
-
-    char *b = (char *)scratch;
-    c->s.hdr = (Header *)b;
-    c->s.cnt = (unsigned long long *)(b + c->off_cnt);
-    for (int i = 0; i < 2; ++i) {
-        c->s.keys[i] = (uint32_t *)(b + c->off_keys[i]);
-        c->s.vals[i] = (uint32_t *)(b + c->off_vals[i]);
-    }
-    c->s.block_hist = (uint32_t *)(b + c->off_hist);
-    c->s.bin_total = (uint32_t *)(b + c->off_bintotal);
-    c->s.long_slot = (uint32_t *)(b + c->off_long_slot);
-    uint32_t *meta = (uint32_t *)(b + c->off_long_meta);
-    c->s.long_head = meta;
-    c->s.long_len = meta + (size_t)c->max_slots;
-    c->s.long_piece = meta + (size_t)2 * c->max_slots;
-    c->s.long_count = meta + (size_t)3 * c->max_slots;
-    c->s.long_base = meta + (size_t)4 * c->max_slots;
-    c->s.piece_slot = (uint32_t *)(b + c->off_piece_slot);
-    c->s.partial = (double *)(b + c->off_partial);
-    c->s.partial2 = c->has_partial2 ? (double *)(b + c->off_partial2) : nullptr;
-    c->s.long_res = (double *)(b + c->off_long_res);
-
-    c->E = E; c->A = A; c->PE = PE; c->PA = PA;
-    c->load_data = (unsigned long long *)load_data;
-    c->load_parity = (unsigned long long *)load_parity;
+    c->s = carve(c->lay, scratch, c->has_partial2);
+    c->t.E = E; c->t.A = A; c->t.PE = PE; c->t.PA = PA;
+    c->t.load_data = (unsigned long long *)load_data;
+    c->t.load_parity = (unsigned long long *)load_parity;
     c->bound = true;
     c->need_init = true;      // the first enqueue clears the header on its stream
     return ECRM_OK;
@@ -217,7 +251,7 @@ int ecrm_encode(ecrm_ctx *c, void *stream)
 {
     if (!c) return ECRM_EINVAL;
     if (!c->bound) return ECRM_ENOTBOUND;
-    launch_encode(c->geo, c->E, c->A, c->PE, c->PA, c->grid_blocks, (hipStream_t)stream);
+    launch_encode(c->geo, c->t.E, c->t.A, c->t.PE, c->t.PA, c->grid_blocks, (hipStream_t)stream);
     return check_launch();
 }
 
@@ -233,31 +267,32 @@ int ecrm_route(ecrm_ctx *c, const uint64_t *keys, uint64_t n, uint64_t *stripe, 
     return check_launch();
 }
 
-// One batch through the whole pipeline.  During a recovery, held-back items are appended to
-// buf[target] (and the key space gets one more value, `rows`, for them to sort behind the rest).
-static int run_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uint32_t n32, uint32_t target,
+// One batch through the whole pipeline, on tables t with scratch s (laid out by l).  During a recovery,
+// held-back items are appended to buf[target] (and the key space gets one more value, `rows`, for them
+// to sort behind the rest).
+static int run_update(ecrm_ctx *c, const Tables &t, const Scratch &s, const Layout &l, const RecoveryView &rv,
+                      bool clear_sticky, const uint64_t *keys, const float *grads, uint32_t n32, uint32_t target,
                       hipStream_t st)
 {
     hipEvent_t *ev = nullptr;
     if (c->profiling && c->ev_calls < ECRM_PROFILE_MAX_CALLS) ev = c->ev[c->ev_calls++];
 
-    launch_reset(c->s, c->geo.S, n32, c->need_init, st);
-    c->need_init = false;
+    launch_reset(s, c->geo.S, n32, clear_sticky, st);
     if (ev) (void)hipEventRecord(ev[0], st);
     int key_bits = c->key_bits;
-    if (c->rv.active)
+    if (rv.active)
         while (key_bits < 32 && (1ull << key_bits) <= c->cfg.rows) ++key_bits;
     const uint32_t prop = c->cfg.propagation;
     uint32_t *sk = nullptr, *si = nullptr;
-    launch_sort(c->s, c->geo, c->rv, keys, n32, key_bits, false, true, &sk, &si, st);
-    if (c->rv.active)
-        launch_hold_back(c->s, c->geo, c->rv, keys, grads, n32, c->buf_keys[target], c->buf_grads[target], c->buf_cap, st);
+    launch_sort(s, c->geo, rv, keys, n32, key_bits, false, true, &sk, &si, st);
+    if (rv.active)
+        launch_hold_back(s, c->geo, rv, keys, grads, n32, c->buf_keys[target], c->buf_grads[target], c->buf_cap, st);
     if (ev) (void)hipEventRecord(ev[1], st);
-    launch_chains(c->s, c->geo, c->A, grads, sk, si, n32, c->max_slots, c->max_pieces, c->cus, st);
+    launch_chains(s, c->geo, c->lg, t.A, grads, sk, si, n32, l.max_slots, l.max_pieces, c->cus, st);
     if (ev) (void)hipEventRecord(ev[2], st);
     const bool diff = prop == ECRM_PROP_DIFFERENCE;
-    launch_apply(c->s, c->geo, c->E, c->A, diff ? c->PE : nullptr, diff ? c->PA : nullptr, c->load_data,
-                 prop == ECRM_PROP_NONE ? nullptr : c->load_parity, grads, sk, si, n32, c->cus, st);
+    launch_apply(s, c->geo, c->lg, t.E, t.A, diff ? t.PE : nullptr, diff ? t.PA : nullptr, t.load_data,
+                 prop == ECRM_PROP_NONE ? nullptr : t.load_parity, grads, sk, si, n32, c->cus, st);
     if (prop == ECRM_PROP_GRADIENT) {
         // The strawman of Sec. 3.3.1: the parity server receives the gradient itself and applies the
         // optimizer to the parity entry with the parity's own state.  The same pipeline once more,
@@ -268,12 +303,12 @@ static int run_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uin
         int bits = 1;
         while (bits < 32 && (1ull << bits) < c->cfg.rows / c->cfg.k) ++bits;
         if (ev) (void)hipEventRecord(ev[3], st);
-        launch_reset(c->s, c->geo.S, n32, false, st);
-        launch_sort(c->s, c->geo, c->rv, keys, n32, bits, true, false, &sk, &si, st);
+        launch_reset(s, c->geo.S, n32, false, st);
+        launch_sort(s, c->geo, rv, keys, n32, bits, true, false, &sk, &si, st);
         if (ev) (void)hipEventRecord(ev[4], st);
-        launch_chains(c->s, gp, c->PA, grads, sk, si, n32, c->max_slots, c->max_pieces, c->cus, st);
+        launch_chains(s, gp, c->lg, t.PA, grads, sk, si, n32, l.max_slots, l.max_pieces, c->cus, st);
         if (ev) (void)hipEventRecord(ev[5], st);
-        launch_apply(c->s, gp, c->PE, c->PA, nullptr, nullptr, nullptr, nullptr, grads, sk, si, n32, c->cus, st);
+        launch_apply(s, gp, c->lg, t.PE, t.PA, nullptr, nullptr, nullptr, nullptr, grads, sk, si, n32, c->cus, st);
         if (ev) (void)hipEventRecord(ev[6], st);
     } else if (ev) {
         (void)hipEventRecord(ev[3], st);
@@ -281,14 +316,22 @@ static int run_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uin
     return check_launch();
 }
 
+static int run_bound_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uint32_t n32, uint32_t target,
+                            hipStream_t st)
+{
+    const bool clear = c->need_init;
+    c->need_init = false;
+    return run_update(c, c->t, c->s, c->lay, c->rv, clear, keys, grads, n32, target, st);
+}
+
 int ecrm_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uint64_t n, void *stream)
 {
     if (!c) return ECRM_EINVAL;
     if (!c->bound) return ECRM_ENOTBOUND;
-    if (n > c->max_batch) return ECRM_EBATCH;
+    if (n > c->lay.max_batch) return ECRM_EBATCH;
     if (n == 0) return ECRM_OK;
     if (!aligned(keys, 8) || !aligned(grads, 16)) return ECRM_EINVAL;
-    return run_update(c, keys, grads, (uint32_t)n, c->buf_cur, (hipStream_t)stream);
+    return run_bound_update(c, keys, grads, (uint32_t)n, c->buf_cur, (hipStream_t)stream);
 }
 
 int ecrm_recovery_begin(ecrm_ctx *c, uint32_t server, uint32_t chunks, uint64_t *buf_keys, float *buf_grads,
@@ -298,9 +341,12 @@ int ecrm_recovery_begin(ecrm_ctx *c, uint32_t server, uint32_t chunks, uint64_t 
     if (!c->bound) return ECRM_ENOTBOUND;
     if (c->rv.active) return ECRM_ESTATE;
     if (c->cfg.propagation != ECRM_PROP_DIFFERENCE) return ECRM_EINVAL;   // no parities a decoder could trust
+    // Synchronous (combined) training takes ONE step per modified entry and training step; replaying
+    // the waiting updates of several steps in one call would merge them into a single step.
+    if (c->cfg.combine) return ECRM_EINVAL;
     const uint32_t stripes = c->geo.rows / c->geo.k;
     if (server >= c->geo.S || chunks < 1 || chunks > stripes) return ECRM_EINVAL;
-    if (capacity < 1 || capacity > c->max_batch || !aligned(buf_keys, 8) || !aligned(buf_grads, 16)) return ECRM_EINVAL;
+    if (capacity < 1 || capacity > c->lay.max_batch || !aligned(buf_keys, 8) || !aligned(buf_grads, 16)) return ECRM_EINVAL;
     const Divider spc_div = make_divider((stripes + chunks - 1) / chunks);
     if (!divider_ok(spc_div)) return ECRM_EINVAL;
     c->rv.active = 1;
@@ -326,6 +372,7 @@ int ecrm_recovery_lock(ecrm_ctx *c)
     if (!c) return ECRM_EINVAL;
     if (!c->rv.active || c->rv.locked || c->rv.next >= c->rec_chunks) return ECRM_ESTATE;
     c->rv.locked = 1;
+    c->rec_decoded = false;
     return ECRM_OK;
 }
 
@@ -333,17 +380,20 @@ int ecrm_recovery_decode(ecrm_ctx *c, void *stream)
 {
     if (!c) return ECRM_EINVAL;
     if (!c->rv.active || !c->rv.locked) return ECRM_ESTATE;
-    const uint32_t stripes = c->geo.rows / c->geo.k;
-    const uint32_t lo = c->rv.next * c->rv.stripes_per_chunk;
-    const uint32_t hi = lo + c->rv.stripes_per_chunk < stripes ? lo + c->rv.stripes_per_chunk : stripes;
-    launch_recover_range(c->geo, c->E, c->A, c->PE, c->PA, c->rv.server, lo, hi, c->grid_blocks, (hipStream_t)stream);
-    return check_launch();
+    const uint64_t stripes = c->geo.rows / c->geo.k;
+    const uint64_t lo = (uint64_t)c->rv.next * c->rv.stripes_per_chunk;
+    const uint64_t hi = lo + c->rv.stripes_per_chunk < stripes ? lo + c->rv.stripes_per_chunk : stripes;
+    launch_recover_range(c->geo, c->t.E, c->t.A, c->t.PE, c->t.PA, c->rv.server, (uint32_t)lo, (uint32_t)hi, c->grid_blocks,
+                         (hipStream_t)stream);
+    const int rc = check_launch();
+    if (rc == ECRM_OK) c->rec_decoded = true;
+    return rc;
 }
 
 int ecrm_recovery_unlock(ecrm_ctx *c, void *stream)
 {
     if (!c) return ECRM_EINVAL;
-    if (!c->rv.active || !c->rv.locked) return ECRM_ESTATE;
+    if (!c->rv.active || !c->rv.locked || !c->rec_decoded) return ECRM_ESTATE;   // nothing rebuilt: lost rows would be trained on
     hipStream_t st = (hipStream_t)stream;
     // how much is waiting: the only synchronisation of the recovery protocol
     if (hipStreamSynchronize(st) != hipSuccess) return ECRM_EHIP;
@@ -357,7 +407,7 @@ int ecrm_recovery_unlock(ecrm_ctx *c, void *stream)
     launch_set_buf_count(c->s, 0, st);
     int rc = check_launch();
     if (rc == ECRM_OK && waiting)
-        rc = run_update(c, (const uint64_t *)c->buf_keys[src], c->buf_grads[src], waiting, c->buf_cur, st);
+        rc = run_bound_update(c, (const uint64_t *)c->buf_keys[src], c->buf_grads[src], waiting, c->buf_cur, st);
     if (c->rv.next >= c->rec_chunks) c->rv.active = 0;       // every chunk is rebuilt, nothing can be waiting any more
     return rc;
 }
@@ -387,7 +437,7 @@ int ecrm_recovery_read(ecrm_ctx *c, const uint64_t *keys, uint64_t n, float *out
     hipStream_t st = (hipStream_t)stream;
     init_if_needed(c, st);
     if (!c->rv.active) {                       // no recovery in progress: a plain gather
-        launch_degraded_read(c->s, c->geo, c->E, c->A, c->PE, c->PA, keys, n, ECRM_NO_SERVER, out_E, out_A,
+        launch_degraded_read(c->s, c->geo, c->t.E, c->t.A, c->t.PE, c->t.PA, keys, n, ECRM_NO_SERVER, out_E, out_A,
                              c->grid_blocks, st);
         return check_launch();
     }
@@ -402,7 +452,7 @@ int ecrm_recovery_read(ecrm_ctx *c, const uint64_t *keys, uint64_t n, float *out
         memset(&none, 0, sizeof(none));
         launch_sort(c->s, c->geo, none, (const uint64_t *)c->buf_keys[c->buf_cur], m, c->key_bits, false, false, &bk, &bi, st);
     }
-    launch_recovery_read(c->s, c->geo, c->rv, c->E, c->A, c->PE, c->PA, keys, n, bk, bi, m, c->buf_grads[c->buf_cur],
+    launch_recovery_read(c->s, c->geo, c->rv, c->t.E, c->t.A, c->t.PE, c->t.PA, keys, n, bk, bi, m, c->buf_grads[c->buf_cur],
                          out_E, out_A, c->grid_blocks, st);
     return check_launch();
 }
@@ -412,7 +462,7 @@ int ecrm_fail_server(ecrm_ctx *c, uint32_t server, void *stream)
     if (!c) return ECRM_EINVAL;
     if (!c->bound) return ECRM_ENOTBOUND;
     if (server >= c->geo.S) return ECRM_EINVAL;
-    launch_fail_server(c->geo, c->E, c->A, c->PE, c->PA, server, c->grid_blocks, (hipStream_t)stream);
+    launch_fail_server(c->geo, c->t.E, c->t.A, c->t.PE, c->t.PA, server, c->grid_blocks, (hipStream_t)stream);
     return check_launch();
 }
 
@@ -421,7 +471,7 @@ int ecrm_recover_server(ecrm_ctx *c, uint32_t server, void *stream)
     if (!c) return ECRM_EINVAL;
     if (!c->bound) return ECRM_ENOTBOUND;
     if (server >= c->geo.S) return ECRM_EINVAL;
-    launch_recover_server(c->geo, c->E, c->A, c->PE, c->PA, server, c->grid_blocks, (hipStream_t)stream);
+    launch_recover_server(c->geo, c->t.E, c->t.A, c->t.PE, c->t.PA, server, c->grid_blocks, (hipStream_t)stream);
     return check_launch();
 }
 
@@ -434,7 +484,7 @@ int ecrm_degraded_read(ecrm_ctx *c, const uint64_t *keys, uint64_t n, uint32_t l
     if (n == 0) return ECRM_OK;
     if (!aligned(keys, 8) || !aligned(out_E, 16) || (out_A && !aligned(out_A, 16))) return ECRM_EINVAL;
     init_if_needed(c, (hipStream_t)stream);
-    launch_degraded_read(c->s, c->geo, c->E, c->A, c->PE, c->PA, keys, n, lost_server, out_E, out_A,
+    launch_degraded_read(c->s, c->geo, c->t.E, c->t.A, c->t.PE, c->t.PA, keys, n, lost_server, out_E, out_A,
                          c->grid_blocks, (hipStream_t)stream);
     return check_launch();
 }

@@ -132,6 +132,14 @@ struct Geometry {
     Divider dk, dS;        // by k and by S
 };
 
+// Grid sizes of the grid-stride kernels for one geometry: exactly the blocks that are resident at
+// once.  Filled once per context when it learns its device (never inside a stream capture).
+struct LaunchGrids {
+    int p1, p3;            // chain pieces: summaries, steps
+    int apply, rows;       // apply with / without the parity rows
+};
+bool query_launch_grids(const Geometry &g, int cus, LaunchGrids *out);   // false: an occupancy query failed
+
 // ---- launchers (each checks nothing: the API layer validates shapes before calling) -------------
 void launch_reset(const Scratch &s, uint32_t S, uint32_t n, bool clear_sticky, hipStream_t st);
 void launch_sort(const Scratch &s, const Geometry &g, const RecoveryView &rv, const uint64_t *keys, uint32_t n,
@@ -143,10 +151,10 @@ void launch_hold_back(const Scratch &s, const Geometry &g, const RecoveryView &r
 void launch_recover_range(const Geometry &g, float *E, float *A, float *PE, float *PA, uint32_t server,
                           uint32_t g_lo, uint32_t g_hi, int grid_blocks, hipStream_t st);
 void launch_set_buf_count(const Scratch &s, uint32_t count, hipStream_t st);
-void launch_chains(const Scratch &s, const Geometry &g, const float *A, const float *grads,
+void launch_chains(const Scratch &s, const Geometry &g, const LaunchGrids &lg, const float *A, const float *grads,
                    const uint32_t *sk, const uint32_t *si, uint32_t n, uint32_t max_slots,
                    uint32_t max_pieces, int cus, hipStream_t st);
-void launch_apply(const Scratch &s, const Geometry &g, float *E, float *A, float *PE, float *PA,
+void launch_apply(const Scratch &s, const Geometry &g, const LaunchGrids &lg, float *E, float *A, float *PE, float *PA,
                   unsigned long long *load_data, unsigned long long *load_parity, const float *grads,
                   const uint32_t *sk, const uint32_t *si, uint32_t n, int cus, hipStream_t st);
 void launch_encode(const Geometry &g, const float *E, const float *A, float *PE, float *PA,

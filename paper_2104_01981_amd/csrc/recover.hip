@@ -38,8 +38,10 @@ __global__ __launch_bounds__(256) void fail_server_kernel(float *E, float *A, fl
 {
     const uint32_t nslices = (D + 127u) / 128u;
     const float nan = __builtin_nanf("");
-    const uint32_t w0 = (blockIdx.x * blockDim.x + threadIdx.x) / kWave, nw = (gridDim.x * blockDim.x) / kWave;
-    for (uint32_t g = w0; g < stripes; g += nw) {
+    // 64-bit stripe counter: with close to 2^32 stripes (k = 1) g + nw would wrap a 32-bit one
+    const uint64_t w0 = (blockIdx.x * blockDim.x + threadIdx.x) / kWave, nw = (gridDim.x * blockDim.x) / kWave;
+    for (uint64_t g64 = w0; g64 < stripes; g64 += nw) {
+        const uint32_t g = (uint32_t)g64;
         const int u = unit_on_server(g, k, S, server);
         if (u < 0) continue;
         const rsrc_t r0 = u == (int)k ? row_of(PE, g, D) : row_of(E, (size_t)g * k + u, D);
@@ -90,8 +92,9 @@ __device__ __forceinline__ void rebuild_row(float *T, float *P, uint32_t g, int 
 __global__ __launch_bounds__(256) void recover_server_kernel(float *E, float *A, float *PE, float *PA, uint32_t g_lo,
                                                              uint32_t g_hi, uint32_t D, uint32_t k, uint32_t S, uint32_t server)
 {
-    const uint32_t w0 = (blockIdx.x * blockDim.x + threadIdx.x) / kWave, nw = (gridDim.x * blockDim.x) / kWave;
-    for (uint32_t g = g_lo + w0; g < g_hi; g += nw) {
+    const uint64_t w0 = (blockIdx.x * blockDim.x + threadIdx.x) / kWave, nw = (gridDim.x * blockDim.x) / kWave;
+    for (uint64_t g64 = (uint64_t)g_lo + w0; g64 < g_hi; g64 += nw) {
+        const uint32_t g = (uint32_t)g64;
         const int u = unit_on_server(g, k, S, server);
         if (u < 0) continue;
         rebuild_row(E, PE, g, u, D, k);
@@ -105,8 +108,9 @@ __global__ __launch_bounds__(256) void recover_server_kernel(float *E, float *A,
 __global__ __launch_bounds__(256) void encode_kernel(const float *E, const float *A, float *PE, float *PA, uint32_t stripes,
                                                      uint32_t D, uint32_t k)
 {
-    const uint32_t w0 = (blockIdx.x * blockDim.x + threadIdx.x) / kWave, nw = (gridDim.x * blockDim.x) / kWave;
-    for (uint32_t g = w0; g < stripes; g += nw) {
+    const uint64_t w0 = (blockIdx.x * blockDim.x + threadIdx.x) / kWave, nw = (gridDim.x * blockDim.x) / kWave;
+    for (uint64_t g64 = w0; g64 < stripes; g64 += nw) {
+        const uint32_t g = (uint32_t)g64;
         rebuild_row(const_cast<float *>(E), PE, g, (int)k, D, k);
         rebuild_row(const_cast<float *>(A), PA, g, (int)k, D, k);
     }

@@ -1043,36 +1043,47 @@ __global__ __launch_bounds__(256) void route_kernel(const uint64_t *keys, uint64
 // ================================================================================================
 
 // Blocks of 256 threads of `kernel` that are resident on the whole device at once: the grid-stride
-// kernels are launched with exactly that many, so that every block starts at time zero.
+// kernels are launched with exactly that many, so that every block starts at time zero.  0 = the
+// occupancy query failed.
 template <typename K>
 static int resident_grid(K kernel, int cus)
 {
     int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess || per_cu < 1) per_cu = 4;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess || per_cu < 1) return 0;
     return cus * per_cu;
 }
 
 template <int NC, int MODE>
-static void chains_for(const Scratch &s, const Geometry &g, const float *A, const float *grads,
+static bool grids_for(int cus, LaunchGrids *out)
+{
+    out->p1 = resident_grid(long_piece_kernel<NC, false, MODE>, cus);
+    out->p3 = resident_grid(long_piece_kernel<NC, true, MODE>, cus);
+    if (NC == 1) {
+        out->apply = resident_grid(apply_stripes_kernel_d128<MODE>, cus);
+        out->rows = resident_grid(apply_rows_kernel_d128<MODE>, cus);
+    } else {
+        out->apply = resident_grid(apply_stripes_kernel_d256<MODE>, cus);
+        out->rows = resident_grid(apply_rows_kernel_d256<MODE>, cus);
+    }
+    return out->p1 > 0 && out->p3 > 0 && out->apply > 0 && out->rows > 0;
+}
+
+template <int NC, int MODE>
+static void chains_for(const Scratch &s, const Geometry &g, const LaunchGrids &lg, const float *A, const float *grads,
                        const uint32_t *sk, const uint32_t *si, uint32_t n, uint32_t max_slots,
                        uint32_t max_pieces, int cus, hipStream_t st)
 {
-    static int grid_p1 = 0, grid_p3 = 0;
-    if (!grid_p1) {
-        grid_p1 = resident_grid(long_piece_kernel<NC, false, MODE>, cus);
-        grid_p3 = resident_grid(long_piece_kernel<NC, true, MODE>, cus);
-    }
     const dim3 grid(cus * 8), block(256);
     hipLaunchKernelGGL(long_find_kernel, grid, block, 0, st, sk, n, s.hdr, s.long_slot, s.long_head, max_slots);
     hipLaunchKernelGGL(long_plan_kernel, grid, block, 0, st, sk, n, s.hdr, s.long_head, s.long_len, s.long_piece,
                        s.long_count, s.long_base, s.piece_slot, max_slots, max_pieces);
-    hipLaunchKernelGGL((long_piece_kernel<NC, false, MODE>), dim3(grid_p1), block, 0, st, si, grads, s.hdr, s.long_head,
+    hipLaunchKernelGGL((long_piece_kernel<NC, false, MODE>), dim3(lg.p1), block, 0, st, si, grads, s.hdr, s.long_head,
                        s.long_len, s.long_piece, s.long_base, s.piece_slot, s.partial, s.partial2, max_pieces, g);
     if (!Rule<MODE>::combine) {
         hipLaunchKernelGGL((long_scan_kernel<NC, MODE>), dim3(cus * 2), dim3(kRowWaves * kWave), 0, st, sk, A, s.hdr, s.long_head, s.long_count,
                            s.long_base, s.long_len, s.long_piece, s.partial, s.partial2, s.long_res, max_slots, g);
         if (MODE != kMomentumSeq)        // momentum's steps came out of the scan: no second pass over the gradients
-            hipLaunchKernelGGL((long_piece_kernel<NC, true, MODE>), dim3(grid_p3), block, 0, st, si, grads, s.hdr,
+            hipLaunchKernelGGL((long_piece_kernel<NC, true, MODE>), dim3(lg.p3), block, 0, st, si, grads, s.hdr,
                                s.long_head, s.long_len, s.long_piece, s.long_base, s.piece_slot, s.partial, s.partial2,
                                max_pieces, g);
     }
@@ -1081,25 +1092,14 @@ static void chains_for(const Scratch &s, const Geometry &g, const float *A, cons
 }
 
 template <int NC, int MODE>
-static void apply_for(const ApplyArgs &a, bool parity, int cus, hipStream_t st)
+static void apply_for(const ApplyArgs &a, const LaunchGrids &lg, bool parity, hipStream_t st)
 {
-    static int grid_apply = 0, grid_rows = 0;
     if (parity) {
-        if (NC == 1) {
-            if (!grid_apply) grid_apply = resident_grid(apply_stripes_kernel_d128<MODE>, cus);
-            hipLaunchKernelGGL(apply_stripes_kernel_d128<MODE>, dim3(grid_apply), dim3(256), 0, st, a);
-        } else {
-            if (!grid_apply) grid_apply = resident_grid(apply_stripes_kernel_d256<MODE>, cus);
-            hipLaunchKernelGGL(apply_stripes_kernel_d256<MODE>, dim3(grid_apply), dim3(256), 0, st, a);
-        }
+        if (NC == 1) hipLaunchKernelGGL(apply_stripes_kernel_d128<MODE>, dim3(lg.apply), dim3(256), 0, st, a);
+        else hipLaunchKernelGGL(apply_stripes_kernel_d256<MODE>, dim3(lg.apply), dim3(256), 0, st, a);
     } else {
-        if (NC == 1) {
-            if (!grid_rows) grid_rows = resident_grid(apply_rows_kernel_d128<MODE>, cus);
-            hipLaunchKernelGGL(apply_rows_kernel_d128<MODE>, dim3(grid_rows), dim3(256), 0, st, a);
-        } else {
-            if (!grid_rows) grid_rows = resident_grid(apply_rows_kernel_d256<MODE>, cus);
-            hipLaunchKernelGGL(apply_rows_kernel_d256<MODE>, dim3(grid_rows), dim3(256), 0, st, a);
-        }
+        if (NC == 1) hipLaunchKernelGGL(apply_rows_kernel_d128<MODE>, dim3(lg.rows), dim3(256), 0, st, a);
+        else hipLaunchKernelGGL(apply_rows_kernel_d256<MODE>, dim3(lg.rows), dim3(256), 0, st, a);
     }
 }
 
@@ -1122,15 +1122,22 @@ static void apply_for(const ApplyArgs &a, bool parity, int cus, hipStream_t st)
         }                                                                        \
     } while (0)
 
-void launch_chains(const Scratch &s, const Geometry &g, const float *A, const float *grads,
+bool query_launch_grids(const Geometry &g, int cus, LaunchGrids *out)
+{
+    bool ok = false;
+    ECRM_DISPATCH(ok = grids_for, cus, out);
+    return ok;
+}
+
+void launch_chains(const Scratch &s, const Geometry &g, const LaunchGrids &lg, const float *A, const float *grads,
                    const uint32_t *sk, const uint32_t *si, uint32_t n, uint32_t max_slots,
                    uint32_t max_pieces, int cus, hipStream_t st)
 {
     if (n <= kLongRun) return;    // no row can have more than kLongRun updates
-    ECRM_DISPATCH(chains_for, s, g, A, grads, sk, si, n, max_slots, max_pieces, cus, st);
+    ECRM_DISPATCH(chains_for, s, g, lg, A, grads, sk, si, n, max_slots, max_pieces, cus, st);
 }
 
-void launch_apply(const Scratch &s, const Geometry &g, float *E, float *A, float *PE, float *PA,
+void launch_apply(const Scratch &s, const Geometry &g, const LaunchGrids &lg, float *E, float *A, float *PE, float *PA,
                   unsigned long long *load_data, unsigned long long *load_parity, const float *grads,
                   const uint32_t *sk, const uint32_t *si, uint32_t n, int cus, hipStream_t st)
 {
@@ -1144,7 +1151,7 @@ void launch_apply(const Scratch &s, const Geometry &g, float *E, float *A, float
     a.n = n; a.geo = g;
     if ((g.mode == kAdagradCombine || g.mode == kMomentumCombine) && load_data)      // one load count per modified entry
         hipLaunchKernelGGL(count_rows_kernel, dim3(cus * 8), dim3(256), 0, st, sk, n, s.hdr, s.cnt, g.k, g.S);
-    ECRM_DISPATCH(apply_for, a, parity, cus, st);
+    ECRM_DISPATCH(apply_for, a, lg, parity, st);
 }
 #undef ECRM_DISPATCH
 

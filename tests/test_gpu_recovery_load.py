@@ -22,7 +22,7 @@ def _batch(seed, first, n, R, D, hot_rows):
 @pytest.mark.parametrize("chunks", [1, 4, 10])
 @pytest.mark.parametrize("R,D,k,S,server,opt,comb", [(4 * 3000, 128, 4, 5, 2, 0, 0), (2 * 2500, 128, 2, 5, 0, 0, 0),
                                                       (10 * 400, 256, 10, 11, 7, 0, 0), (4 * 3000, 128, 4, 5, 4, 1, 0),
-                                                      (4 * 3000, 128, 4, 5, 1, 0, 1)])
+                                                      (4 * 3000, 128, 4, 5, 1, 1, 0)])
 def test_training_during_recovery(chunks, R, D, k, S, server, opt, comb):
     n, seed = 20000, 83
     cap = 8 * n                                       # hot lost entries of the last chunk wait through the whole recovery
@@ -99,6 +99,9 @@ def test_recovery_buffer_overflow_and_state_errors():
     assert c.ctx.recovery_unlock(check=False) == -8
     c.ctx.recovery_lock()
     assert c.ctx.recovery_lock(check=False) == -8
+    assert c.ctx.recovery_unlock(check=False) == -8                 # nothing has been decoded under this lock
+    assert c.ctx.bind_raw(c.E.data_ptr(), c.A.data_ptr(), c.PE.data_ptr(), c.PA.data_ptr(), c.ld.data_ptr(),
+                          c.lp.data_ptr(), c.scratch.data_ptr(), c.scratch.numel()) == -8   # would drop the buffer
     before = [t.clone() for t in (c.E, c.A, c.PE, c.PA, c.ld, c.lp)]
     c.ctx.update(kt, g)                                             # far more than 64 items have to wait
     assert c.ctx.status() == -7                                     # ECRM_EBUFFER
@@ -117,7 +120,7 @@ def test_recovery_buffer_overflow_and_state_errors():
 
 @pytest.mark.parametrize("chunks", [1, 4])
 @pytest.mark.parametrize("R,D,k,S,server,opt,comb", [(4 * 3000, 128, 4, 5, 2, 0, 0), (10 * 400, 256, 10, 11, 7, 1, 0),
-                                                      (2 * 2500, 36, 2, 5, 0, 0, 1)])
+                                                      (2 * 2500, 36, 2, 5, 0, 1, 0)])
 def test_reads_during_recovery(chunks, R, D, k, S, server, opt, comb):
     """ecrm_recovery_read against the protocol oracle's read at every stage (before a lock, under it,
     after the decode, after the unlock), and against the tables the replay leaves behind."""
@@ -188,6 +191,15 @@ def test_reads_during_recovery(chunks, R, D, k, S, server, opt, comb):
     both_read("after the recovery")                     # a plain gather again
     assert torch.equal(c.E[sample_t], oe)
     log("reads during recovery", (chunks, R, D, k, S, server, opt, comb), c.compare("session reads"))
+
+
+def test_no_recovery_protocol_for_combined_training():
+    """Synchronous training takes one step per entry and training step (Sec. 4.4); a replayed buffer would
+    merge several steps into one, so the library refuses to start the protocol in that mode."""
+    c = Case(4 * 100, 128, 4, 5, max_batch=100, seed=3, combine=1)
+    bk = torch.empty(200, dtype=torch.int64, device="cuda")
+    bg = torch.empty(200, 128, device="cuda")
+    assert c.ctx.recovery_begin(1, 2, bk, bg, 100, check=False) == -1
 
 
 def test_recovery_read_errors():

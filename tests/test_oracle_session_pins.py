@@ -182,9 +182,11 @@ def test_read_without_waiting_updates_is_the_table_or_the_decoded_entry():
     assert lost.any() and np.isnan(E[lost]).all()
     np.testing.assert_array_equal(gE[~lost], E0[~lost])                   # survivors: the table itself
     np.testing.assert_allclose(gE[lost], E0[lost], rtol=0, atol=2e-7)     # lost ones: decoded, to one rounding of the sum
-    for m in ("optimizer", "combine"):                                    # the other rules go through the same door
+    with pytest.raises(ValueError):                                       # synchronous training: steps must not be merged
+        RecoverySession(E.copy(), A.copy(), PE.copy(), PA.copy(), k, S, 0.01, 1e-8, server, 2, 100, combine=1)
+    for m in ("optimizer",):                                              # momentum SGD goes through the same door
         ses2 = RecoverySession(E.copy(), A.copy(), PE.copy(), PA.copy(), k, S, 0.01, 1e-8, server, 2, 100,
-                               optimizer=1 if m == "optimizer" else 0, momentum=0.9, combine=1 if m == "combine" else 0)
+                               optimizer=1, momentum=0.9, combine=0)
         ses2.lock()
         kk, gg = _batch(rng, R, D, 50)
         assert ses2.update(kk, gg)
