@@ -208,12 +208,21 @@ int ecrm_clear_status(ecrm_ctx *ctx, void *hip_stream);
  * ecrm_batch_stats waits for the stream and reports what the LAST ecrm_update found:
  *   out[0] = entries updated through the split-chain path (more than ECRM_LONG_RUN updates)
  *   out[1] = chain pieces those were cut into,  out[2] = items in those entries,
- *   out[3] = 1 if the batch was rejected for a bad key. */
+ *   out[3] = 1 if the batch was rejected for a bad key.
+ * ecrm_host_placement runs on the HOST only (no GPU needed): it evaluates, with the very 32-bit
+ * arithmetic the kernels use, where `key` lies -- out[0] = stripe, out[1] = member, out[2] = data
+ * server, out[3] = parity server (Sec. 3.2) -- and, for a recovery of `failed_server` in `chunks`
+ * chunks of which `next_chunk` are rebuilt and the next one is locked or not, out[4] = 1 if an update
+ * to `key` would be held back (Sec. 3.4) and out[5] = the unit of its stripe that the failed server
+ * holds (member index, k for the parity, 0xFFFFFFFF for none).  EINVAL for key >= rows, a bad server
+ * or chunk count. */
 enum { ECRM_PHASE_GROUP = 0, ECRM_PHASE_CHAINS = 1, ECRM_PHASE_APPLY = 2, ECRM_PHASES = 3 };
 enum { ECRM_PROFILE_MAX_CALLS = 256, ECRM_LONG_RUN = 1024 };
 int ecrm_profile(ecrm_ctx *ctx, int enable);
 int ecrm_profile_read(ecrm_ctx *ctx, double *ms, uint64_t *calls);
 int ecrm_batch_stats(ecrm_ctx *ctx, void *hip_stream, uint64_t *out);
+int ecrm_host_placement(const ecrm_ctx *ctx, uint64_t key, uint32_t failed_server, uint32_t chunks,
+                        uint32_t next_chunk, uint32_t locked, uint32_t *out /*[6]*/);
 
 const char *ecrm_strerror(int code);
 

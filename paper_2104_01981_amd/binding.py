@@ -19,7 +19,7 @@ _lib = None
 
 SYMBOLS = ["ecrm_create", "ecrm_destroy", "ecrm_data_bytes", "ecrm_parity_bytes", "ecrm_scratch_bytes",
            "ecrm_bind", "ecrm_encode", "ecrm_route", "ecrm_update", "ecrm_status", "ecrm_clear_status",
-           "ecrm_profile", "ecrm_profile_read", "ecrm_batch_stats", "ecrm_strerror",
+           "ecrm_profile", "ecrm_profile_read", "ecrm_batch_stats", "ecrm_host_placement", "ecrm_strerror",
            "ecrm_fail_server", "ecrm_recover_server", "ecrm_degraded_read",
            "ecrm_recovery_begin", "ecrm_recovery_lock", "ecrm_recovery_decode", "ecrm_recovery_unlock",
            "ecrm_recovery_state", "ecrm_recovery_read"]
@@ -74,6 +74,8 @@ def load_library():
         lib.ecrm_profile.argtypes = [vp, C.c_int]
         lib.ecrm_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
         lib.ecrm_batch_stats.argtypes = [vp, vp, C.POINTER(C.c_uint64)]
+        lib.ecrm_host_placement.argtypes = [vp, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
+                                            C.POINTER(C.c_uint32)]
         lib.ecrm_strerror.argtypes = [C.c_int]
         lib.ecrm_strerror.restype = C.c_char_p
         _lib = lib
@@ -247,6 +249,14 @@ class Ecrm:
         if rc != ECRM_OK:
             raise EcrmError(rc, "ecrm_profile_read")
         return list(ms), int(calls.value)
+
+    def host_placement(self, key, failed_server, chunks, next_chunk, locked):
+        out = (C.c_uint32 * 6)()
+        rc = self._lib.ecrm_host_placement(self._ctx, C.c_uint64(key), C.c_uint32(failed_server), C.c_uint32(chunks),
+                                           C.c_uint32(next_chunk), C.c_uint32(1 if locked else 0), out)
+        if rc != ECRM_OK:
+            raise EcrmError(rc, "ecrm_host_placement")
+        return [int(v) for v in out]
 
     def batch_stats(self, stream=None):
         out = (C.c_uint64 * 4)()

@@ -143,7 +143,7 @@ int ecrm_create(const ecrm_config *cfg, ecrm_ctx **out)
     if (!cfg || !out) return ECRM_EINVAL;
     *out = nullptr;
     if (cfg->k < 1 || cfg->k > 64) return ECRM_EINVAL;
-    if (cfg->rows < cfg->k || cfg->rows % cfg->k != 0 || cfg->rows > 0xFFFFFFFFull - 4096) return ECRM_EINVAL;
+    if (cfg->rows < cfg->k || cfg->rows % cfg->k != 0 || cfg->rows > 0x100000000ull - 4096) return ECRM_EINVAL;
     if (cfg->dim < 4 || cfg->dim > 1024 || cfg->dim % 4 != 0) return ECRM_EINVAL;
     if (cfg->servers < cfg->k + 1 || cfg->servers > 1024) return ECRM_EINVAL;
     if (cfg->optimizer != ECRM_OPT_ADAGRAD && cfg->optimizer != ECRM_OPT_MOMENTUM) return ECRM_EINVAL;
@@ -347,15 +347,16 @@ int ecrm_recovery_begin(ecrm_ctx *c, uint32_t server, uint32_t chunks, uint64_t 
     const uint32_t stripes = c->geo.rows / c->geo.k;
     if (server >= c->geo.S || chunks < 1 || chunks > stripes) return ECRM_EINVAL;
     if (capacity < 1 || capacity > c->lay.max_batch || !aligned(buf_keys, 8) || !aligned(buf_grads, 16)) return ECRM_EINVAL;
-    const Divider spc_div = make_divider((stripes + chunks - 1) / chunks);
+    const uint32_t spc = (uint32_t)(((uint64_t)stripes + chunks - 1) / chunks);   // 64-bit: the sum can pass 2^32
+    const Divider spc_div = make_divider(spc);
     if (!divider_ok(spc_div)) return ECRM_EINVAL;
     c->rv.active = 1;
     c->rv.server = server;
     c->rv.next = 0;
     c->rv.locked = 0;
-    c->rv.stripes_per_chunk = (stripes + chunks - 1) / chunks;
+    c->rv.stripes_per_chunk = spc;
     c->rv.dspc = spc_div;
-    c->rec_chunks = (stripes + c->rv.stripes_per_chunk - 1) / c->rv.stripes_per_chunk;
+    c->rec_chunks = (uint32_t)(((uint64_t)stripes + spc - 1) / spc);
     c->buf_cap = (uint32_t)capacity;
     c->buf_cur = 0;
     c->buf_keys[0] = (unsigned long long *)buf_keys;
@@ -523,6 +524,35 @@ int ecrm_batch_stats(ecrm_ctx *c, void *stream, uint64_t *out)
     out[1] = h.n_pieces;
     out[2] = h.n_long_items;
     out[3] = h.batch_bad;
+    return ECRM_OK;
+}
+
+// Host-side evaluation of the 32-bit index arithmetic the kernels use (the multiply-and-shift
+// divisions, the hold-back rule, the unit a server holds): the same inline functions, compiled for
+// the host, so that a test can compare them with plain 64-bit arithmetic over the whole row range.
+int ecrm_host_placement(const ecrm_ctx *c, uint64_t key, uint32_t failed_server, uint32_t chunks,
+                        uint32_t next_chunk, uint32_t locked, uint32_t *out)
+{
+    if (!c || !out || key >= c->cfg.rows || failed_server >= c->geo.S) return ECRM_EINVAL;
+    const uint32_t stripes = c->geo.rows / c->geo.k;
+    if (chunks < 1 || chunks > stripes) return ECRM_EINVAL;
+    const uint32_t x = (uint32_t)key, k = c->geo.k;
+    const uint32_t g = c->geo.dk.div(x), j = x - g * k;
+    out[0] = g;
+    out[1] = j;
+    out[2] = c->geo.dS.mod(g + 1 + j);
+    out[3] = c->geo.dS.mod(g);
+    RecoveryView rv;
+    memset(&rv, 0, sizeof(rv));
+    rv.active = 1;
+    rv.server = failed_server;
+    rv.next = next_chunk;
+    rv.locked = locked ? 1u : 0u;
+    rv.stripes_per_chunk = (uint32_t)(((uint64_t)stripes + chunks - 1) / chunks);
+    rv.dspc = make_divider(rv.stripes_per_chunk);
+    if (!divider_ok(rv.dspc)) return ECRM_EINVAL;
+    out[4] = held_back(rv, x, c->geo.dk, c->geo.dS) ? 1u : 0u;
+    out[5] = (uint32_t)unit_on_server(g, k, c->geo.S, failed_server);
     return ECRM_OK;
 }
 

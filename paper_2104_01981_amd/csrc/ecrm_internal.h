@@ -121,6 +121,15 @@ __host__ __device__ __forceinline__ bool held_back(const RecoveryView &r, uint32
     return lost == j;                                 // not rebuilt yet: only the lost entry itself waits
 }
 
+// which unit of stripe g does `server` hold: -1 none, k the parity, j < k member j
+__host__ __device__ __forceinline__ int unit_on_server(uint32_t g, uint32_t k, uint32_t S, uint32_t server)
+{
+    const uint32_t p = g % S;
+    if (p == server) return (int)k;
+    const uint32_t j = (server + S - (p + 1u) % S) % S;      // (g+1+j) mod S == server  <=>  j == server - (p+1) mod S
+    return j < k ? (int)j : -1;
+}
+
 struct Geometry {
     uint32_t D, k, S;
     uint32_t rows;         // R (< 2^32)

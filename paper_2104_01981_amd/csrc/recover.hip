@@ -24,15 +24,6 @@ __device__ __forceinline__ void str(rsrc_t r, uint32_t slice, float2 v)
 }
 __device__ __forceinline__ uint32_t uni(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
 
-// which unit of stripe g does `server` hold: -1 none, k the parity, j < k member j
-__device__ __forceinline__ int unit_on_server(uint32_t g, uint32_t k, uint32_t S, uint32_t server)
-{
-    const uint32_t p = g % S;
-    if (p == server) return (int)k;
-    const uint32_t j = (server + S - (p + 1u) % S) % S;      // (g+1+j) mod S == server  <=>  j == server - (p+1) mod S
-    return j < k ? (int)j : -1;
-}
-
 __global__ __launch_bounds__(256) void fail_server_kernel(float *E, float *A, float *PE, float *PA, uint32_t stripes,
                                                           uint32_t D, uint32_t k, uint32_t S, uint32_t server)
 {

@@ -47,6 +47,10 @@ class Case:
         """keys_np: u64 host array; grads_t: [n, D] fp32 device tensor.  Runs both sides."""
         keys_t = torch.from_numpy(keys_np.view(np.int64)).to("cuda:0")
         self.ctx.update(keys_t, grads_t, n=len(keys_np))
+        self.oracle_update(keys_np, grads_t)
+
+    def oracle_update(self, keys_np, grads_t):
+        """The oracle's side of update() alone."""
         if self.propagation == 1:       # gradient propagation: the strawman, counted like the real thing
             oracle.update_gradient_propagation_rule(self.hE, self.hA, self.hPE, self.hPA, self.k, self.lr, self.eps,
                                                     keys_np, grads_t.cpu().numpy(), self.optimizer, self.momentum)

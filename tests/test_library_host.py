@@ -82,3 +82,51 @@ def test_scratch_grows_with_batch(lib):
         lib.ecrm_destroy(ctx)
     assert sizes[0] < sizes[1] < sizes[2]
     assert sizes[2] < (1 << 20) * 64          # well under 64 B per item
+
+
+def _placement_ref(x, R, k, S, server, chunks, nxt, locked):
+    """Placement (Sec. 3.2) and the hold-back rule (Sec. 3.4) in unbounded Python integers."""
+    g, j = x // k, x % k
+    ds, ps = (g + 1 + j) % S, g % S
+    stripes = R // k
+    spc = -(-stripes // chunks)
+    if ps == server:
+        unit = k
+    else:
+        unit = next((m for m in range(k) if (g + 1 + m) % S == server), -1)
+    c = g // spc
+    held = unit >= 0 and c >= nxt and ((c == nxt and locked) or unit == j)
+    return [g, j, ds, ps, int(held), unit & 0xFFFFFFFF]
+
+
+@pytest.mark.parametrize("R,k,S", [((1 << 32) - 4096, 1, 2), ((1 << 32) - 4096, 4, 5), ((1 << 32) - 4096 - 64, 64, 65),
+                                   ((1 << 31) + 4096, 1, 3), (((1 << 32) - 4096) // 10 * 10, 10, 11),
+                                   ((1 << 32) - 4096 - 3, 3, 1024), (1 << 25, 4, 5)])
+def test_index_arithmetic_at_the_top_of_the_row_range(lib, R, k, S):
+    """The kernels divide by k, S and the chunk size with 32-bit multiply-and-shift; rows go up to
+    2^32 - 4096.  Same answers as unbounded integer arithmetic at both ends of the range, around 2^31,
+    around multiples of k*S, and on a spread of other rows."""
+    import random
+    rc, ctx = _create(lib, rows=R, k=k, servers=S, dim=4)
+    assert rc == 0
+    rnd = random.Random(R ^ k ^ S)
+    xs = set()
+    for base in (0, k * S, 1 << 31, (1 << 31) // (k * S) * (k * S), R - 1, R // 2, R - k * S):
+        for d in range(-3 * k - 2, 3 * k + 3):
+            if 0 <= base + d < R:
+                xs.add(base + d)
+    xs.update(rnd.randrange(R) for _ in range(1500))
+    xs.update(rnd.randrange(max(0, R - (1 << 20)), R) for _ in range(500))
+    out = (C.c_uint32 * 6)()
+    stripes = R // k
+    for chunks in (1, 7, 1000, min(stripes, 5000)):
+        spc = -(-stripes // chunks)
+        nchunks = -(-stripes // spc)
+        for x in xs:
+            server = rnd.randrange(S)
+            nxt = rnd.choice([0, nchunks - 1, rnd.randrange(nchunks), (x // k) // spc])
+            locked = rnd.random() < 0.5
+            assert lib.ecrm_host_placement(ctx, x, server, chunks, nxt, 1 if locked else 0, out) == 0
+            assert list(out) == _placement_ref(x, R, k, S, server, chunks, nxt, locked), (x, server, chunks, nxt, locked)
+    assert lib.ecrm_host_placement(ctx, R, 0, 1, 0, 0, out) == binding.ECRM_EINVAL
+    lib.ecrm_destroy(ctx)
