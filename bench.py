@@ -545,7 +545,7 @@ def main():
         buf_grads = torch.empty(2 * per, D, device=dev)
         side, main = torch.cuda.Stream(), torch.cuda.current_stream()
         under_load = {}
-        for chunks in (1, 10):
+        for chunks in (() if args.combine else (1, 10)):    # the protocol is defined for asynchronous training only
             ctx.recovery_begin(0, chunks, buf_keys, buf_grads, per)
             torch.cuda.synchronize()
             tr0 = time.perf_counter()
