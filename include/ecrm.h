@@ -124,6 +124,27 @@ int ecrm_route(ecrm_ctx *ctx, const uint64_t *keys, uint64_t n, uint64_t *stripe
  * keys/grads may be reused once the stream has passed the call. */
 int ecrm_update(ecrm_ctx *ctx, const uint64_t *keys, const float *grads, uint64_t n, void *hip_stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc: ecrm_update with the library's own
+ * scratch buffer, a fixed array of ECRM_STATIC_SCRATCH_BYTES in the library's image (every GPU the
+ * library runs on holds its copy until the process ends).  The call allocates and frees nothing.
+ * The context supplies the configuration only (ecrm_bind is not needed and bound buffers are not
+ * touched); tables, counters, keys and gradients are passed here, with the meaning, layout and
+ * alignment they have in ecrm_bind / ecrm_update.  With ECRM_PROP_NONE, PE, PA and load_parity may be
+ * NULL.  Limits: n <= ECRM_STATIC_MAX_BATCH (else EBATCH), and a configuration whose scratch layout
+ * for that batch size exceeds the array (large dim with momentum SGD) is refused with ESCRATCH; no
+ * recovery may be in progress on the context (ESTATE).
+ * The array has no sticky status: every call starts from a cleared header.  *rejected (DEVICE memory, 4
+ * bytes, may be NULL) receives 1 if the batch carried a key >= rows -- then nothing of it was applied --
+ * and 0 otherwise, in stream order.  All calls on one GPU share the one array: calls that overlap in
+ * time on the same GPU (two streams, two contexts, two threads) race; serialise them.
+ * The first call of a context, and the first on each device, do one-time host-side set-up (occupancy
+ * queries, the array's address): make that call outside a stream capture. */
+enum { ECRM_STATIC_MAX_BATCH = 1 << 16, ECRM_STATIC_SCRATCH_BYTES = 8 << 20 };
+int ecrm_update_static(ecrm_ctx *ctx, float *E, float *A, float *PE, float *PA, uint64_t *load_data,
+                       uint64_t *load_parity, const uint64_t *keys, const float *grads, uint64_t n,
+                       uint32_t *rejected, void *hip_stream);
+
 /* Recovery from the loss of one server (Sec. 3.4), with the subtraction decoder of Sec. 3.2:
  * a lost entry is e_j = p - sum_{i != j} e_i (same for its accumulator), a lost parity is re-encoded.
  * Server s holds member j of stripe g when (g+1+j) mod S == s and the parity of g when g mod S == s;

@@ -18,7 +18,7 @@ _LIB_PATH = os.environ.get("ECRM_LIBRARY") or os.path.join(_HERE, "libecrm.so")
 _lib = None
 
 SYMBOLS = ["ecrm_create", "ecrm_destroy", "ecrm_data_bytes", "ecrm_parity_bytes", "ecrm_scratch_bytes",
-           "ecrm_bind", "ecrm_encode", "ecrm_route", "ecrm_update", "ecrm_status", "ecrm_clear_status",
+           "ecrm_bind", "ecrm_encode", "ecrm_route", "ecrm_update", "ecrm_update_static", "ecrm_status", "ecrm_clear_status",
            "ecrm_profile", "ecrm_profile_read", "ecrm_batch_stats", "ecrm_host_placement", "ecrm_strerror",
            "ecrm_fail_server", "ecrm_recover_server", "ecrm_degraded_read",
            "ecrm_recovery_begin", "ecrm_recovery_lock", "ecrm_recovery_decode", "ecrm_recovery_unlock",
@@ -59,6 +59,7 @@ def load_library():
         lib.ecrm_encode.argtypes = [vp, vp]
         lib.ecrm_route.argtypes = [vp, u64p, C.c_uint64, u64p, u32p, u32p, u32p, vp]
         lib.ecrm_update.argtypes = [vp, u64p, f32p, C.c_uint64, vp]
+        lib.ecrm_update_static.argtypes = [vp, f32p, f32p, f32p, f32p, u64p, u64p, u64p, f32p, C.c_uint64, u32p, vp]
         lib.ecrm_fail_server.argtypes = [vp, C.c_uint32, vp]
         lib.ecrm_recover_server.argtypes = [vp, C.c_uint32, vp]
         lib.ecrm_degraded_read.argtypes = [vp, u64p, C.c_uint64, C.c_uint32, f32p, f32p, vp]
@@ -169,6 +170,17 @@ class Ecrm:
         rc = self._lib.ecrm_update(self._ctx, _ptr(keys), _ptr(grads), C.c_uint64(n), _stream(stream))
         if check and rc != ECRM_OK:
             raise EcrmError(rc, "ecrm_update")
+        return rc
+
+    def update_static(self, E, A, PE, PA, load_data, load_parity, keys, grads, n=None, rejected=None, stream=None,
+                      check=True):
+        """ecrm_update_static: the library's own fixed scratch array, tables passed per call."""
+        n = keys.numel() if n is None else n
+        rc = self._lib.ecrm_update_static(self._ctx, _ptr(E), _ptr(A), _ptr(PE), _ptr(PA), _ptr(load_data),
+                                          _ptr(load_parity), _ptr(keys), _ptr(grads), C.c_uint64(n), _ptr(rejected),
+                                          _stream(stream))
+        if check and rc != ECRM_OK:
+            raise EcrmError(rc, "ecrm_update_static")
         return rc
 
     def fail_server(self, server, stream=None):

@@ -1,6 +1,7 @@
 // C ABI of libecrm: argument validation, scratch layout, and the order in which the kernels of one
 // call are enqueued.  No device memory is allocated here; everything lives in caller buffers.
 #include <math.h>
+#include <mutex>
 #include <new>
 #include <string.h>
 
@@ -27,12 +28,13 @@ struct ecrm_ctx {
     Geometry geo;
     int key_bits;
     Layout lay;               // of the scratch buffer the caller binds (sized by cfg.max_batch)
+    Layout slay;              // of the library's own fixed scratch array (ecrm_update_static)
     bool has_partial2;
     // bound state
     bool bound, need_init;
     Tables t;
     Scratch s;
-    bool have_device;         // cus, grid sizes known (ecrm_bind)
+    bool have_device;         // cus, grid sizes known (ecrm_bind, or the first ecrm_update_static)
     int grid_blocks;          // 8 blocks of 256 threads per CU, for the streaming kernels
     int cus;
     LaunchGrids lg;           // resident grids of the grid-stride kernels (filled by ecrm_bind)
@@ -178,6 +180,7 @@ int ecrm_create(const ecrm_config *cfg, ecrm_ctx **out)
     while (c->key_bits < 32 && (1ull << c->key_bits) < cfg->rows) ++c->key_bits;
     c->has_partial2 = cfg->optimizer == ECRM_OPT_MOMENTUM && !cfg->combine;
     c->lay = make_layout((uint32_t)cfg->max_batch, cfg->dim, cfg->servers, c->has_partial2);
+    c->slay = make_layout(ECRM_STATIC_MAX_BATCH, cfg->dim, cfg->servers, c->has_partial2);
     *out = c;
     return ECRM_OK;
 }
@@ -332,6 +335,77 @@ int ecrm_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uint64_t 
     if (n == 0) return ECRM_OK;
     if (!aligned(keys, 8) || !aligned(grads, 16)) return ECRM_EINVAL;
     return run_bound_update(c, keys, grads, (uint32_t)n, c->buf_cur, (hipStream_t)stream);
+}
+
+// ---- ecrm_update for callers that cannot provide a scratch buffer --------------------------------
+// The scratch buffer of this entry point lives in the library's image: one copy per GPU, held until the
+// process ends.  In host code the array's name is only a handle: the device address comes from
+// hipGetSymbolAddress, once per device, and only that pointer is ever handed to a kernel.
+static __device__ __align__(256) unsigned char g_static_scratch[ECRM_STATIC_SCRATCH_BYTES];
+
+enum { kMaxDevices = 64 };
+static void *g_static_ptr[kMaxDevices];          // device address of g_static_scratch on each device
+static std::mutex g_static_mutex;
+
+static int static_scratch_of_current_device(void **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ECRM_EHIP;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)) != hipSuccess || !p) return ECRM_EHIP;
+        g_static_ptr[dev] = p;
+    }
+    *out = g_static_ptr[dev];
+    return ECRM_OK;
+}
+
+// h == nullptr: an empty batch, nothing can have been rejected
+__global__ void publish_rejected_kernel(const Header *h, uint32_t *rejected)
+{
+    if (threadIdx.x == 0) *rejected = h ? h->batch_bad : 0u;
+}
+
+int ecrm_update_static(ecrm_ctx *c, float *E, float *A, float *PE, float *PA, uint64_t *load_data,
+                       uint64_t *load_parity, const uint64_t *keys, const float *grads, uint64_t n,
+                       uint32_t *rejected, void *stream)
+{
+    if (!c) return ECRM_EINVAL;
+    if (c->rv.active) return ECRM_ESTATE;              // the recovery protocol lives in the bound scratch buffer
+    if (n > ECRM_STATIC_MAX_BATCH) return ECRM_EBATCH;
+    if (c->slay.bytes > ECRM_STATIC_SCRATCH_BYTES) return ECRM_ESCRATCH;   // this geometry needs more than the fixed array
+    if (!aligned(E, 16) || !aligned(A, 16) || !aligned(load_data, 8)) return ECRM_EINVAL;
+    if (c->cfg.propagation != ECRM_PROP_NONE && (!aligned(PE, 16) || !aligned(PA, 16) || !aligned(load_parity, 8)))
+        return ECRM_EINVAL;
+    if (rejected && !aligned(rejected, 4)) return ECRM_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    if (n == 0) {
+        if (!rejected) return ECRM_OK;
+        hipLaunchKernelGGL(publish_rejected_kernel, dim3(1), dim3(64), 0, st, (const Header *)nullptr, rejected);
+        return check_launch();
+    }
+    if (!aligned(keys, 8) || !aligned(grads, 16)) return ECRM_EINVAL;
+    int rc = learn_device(c);
+    if (rc != ECRM_OK) return rc;
+    void *base = nullptr;
+    rc = static_scratch_of_current_device(&base);
+    if (rc != ECRM_OK) return rc;
+    const Scratch s = carve(c->slay, base, c->has_partial2);
+    Tables t;
+    t.E = E; t.A = A; t.PE = PE; t.PA = PA;
+    t.load_data = (unsigned long long *)load_data;
+    t.load_parity = (unsigned long long *)load_parity;
+    RecoveryView none;
+    memset(&none, 0, sizeof(none));
+    // the array keeps the last call's contents: the reset kernel clears every field of the header,
+    // the per-server counts and (clear_sticky) the status word; everything else is written before it is read
+    rc = run_update(c, t, s, c->slay, none, true, keys, grads, (uint32_t)n, 0, st);
+    if (rc == ECRM_OK && rejected) {
+        hipLaunchKernelGGL(publish_rejected_kernel, dim3(1), dim3(64), 0, st, s.hdr, rejected);
+        rc = check_launch();
+    }
+    return rc;
 }
 
 int ecrm_recovery_begin(ecrm_ctx *c, uint32_t server, uint32_t chunks, uint64_t *buf_keys, float *buf_grads,
