@@ -59,6 +59,46 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def memory_ceilings(torch, dev):
+    """Rates of the plainest memory-bound kernels on this device, in GB/s of bytes read plus bytes written:
+    an 8 GiB device-to-device copy; a gather of random 512-byte rows out of an 8 GiB table; and the
+    read-modify-write of such rows (gather, then scatter back), which is the access pattern of the
+    update path's tables."""
+    def timed(fn, reps=5):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+    rows, width = 1 << 24, 128                                    # 8 GiB of 512-byte rows
+    src = torch.zeros(rows, width, device=dev)
+    dst = torch.empty_like(src)
+    copy_s = timed(lambda: dst.copy_(src))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(99)
+    m = 1 << 22                                                   # 2 GiB worth of distinct random rows
+    idx = torch.randperm(rows, device=dev, generator=gen)[:m]
+    buf = torch.empty(m, width, device=dev)
+    gather_s = timed(lambda: torch.index_select(src, 0, idx, out=buf))
+
+    def rmw():
+        torch.index_select(src, 0, idx, out=buf)
+        src.index_copy_(0, idx, buf)
+    rmw_s = timed(rmw)
+    nbytes = rows * width * 4
+    res = {"copy_ceiling_GBps": 2 * nbytes / copy_s / 1e9,
+           "row_gather_ceiling_GBps": 2 * m * width * 4 / gather_s / 1e9,
+           "row_rmw_ceiling_GBps": 4 * m * width * 4 / rmw_s / 1e9,
+           "what": "8 GiB copy; gather of 2^22 random 512-byte rows of an 8 GiB table into a dense buffer; the same "
+                   "rows gathered and scattered back (two kernels); bytes read + written per second"}
+    del src, dst, buf, idx
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -80,6 +120,11 @@ def main():
                          "batches); phase timers are not available in this mode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-recovery", action="store_true", help="skip the recovery-decode measurement")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the plain-copy and random-row ceilings of the device memory")
+    ap.add_argument("--separate-figure", type=int, default=-1,
+                    help="1: after the main measurement, measure the same update with one plain allocation per array "
+                         "and report it beside the arena's figure (default: on for the large workloads)")
     ap.add_argument("--layout", default="auto", choices=["auto", "probed", "arena", "separate"],
                     help="auto: the built-in list of layouts, one per placement trial; arena: one arena in --order; "
                          "probed: one allocation per array, each kept only if a random-row read probe finds it in "
@@ -146,6 +191,8 @@ def main():
     if args.propagation != "difference":
         variant += f"/{args.propagation}-propagation"
     prop = {"difference": 0, "gradient": 1, "none": 2}[args.propagation]
+    if args.separate_figure < 0:
+        args.separate_figure = 1 if (w["n"] >> sh) >= (1 << 26) else 0
     if args.placement_accept_frac is None:
         args.placement_accept_frac = 0.70 if (args.workload == "hbm_scale" and not sh and not variant) else 0.0
 
@@ -406,11 +453,16 @@ def main():
         f"scratch {ctx.scratch_bytes() / 2**20:.0f} MiB, "
         f"alg bytes/item path {sum(alg_path) / (per * nb):.1f}")
 
-    # host copy of the first 1/16 of the stripes for the CPU baseline (taken before any update)
+    # host copy of the first 1/16 of the stripes for the CPU baseline (taken before any update), and of
+    # the updates of the first batches that fall on it
     shard_rows = max(k, (R // 16) // k * k)
+    cpu_batches = []
     if not args.no_cpu_baseline:
         hE, hA = E[:shard_rows].cpu().numpy(), A[:shard_rows].cpu().numpy()
         hPE, hPA = PE[:shard_rows // k].cpu().numpy(), PA[:shard_rows // k].cpu().numpy()
+        for b in range(min(nb, 4)):
+            sel = torch.nonzero(keys[b] < shard_rows).squeeze(1)
+            cpu_batches.append((keys[b][sel].cpu().numpy().view(np.uint64), grads[b][sel].cpu().numpy()))
 
     for i in range(-args.warmup, 0):
         ctx.update(keys[i % nb], grads[i % nb])
@@ -545,7 +597,9 @@ def main():
         buf_grads = torch.empty(2 * per, D, device=dev)
         side, main = torch.cuda.Stream(), torch.cuda.current_stream()
         under_load = {}
-        for chunks in (() if args.combine else (1, 10)):    # the protocol is defined for asynchronous training only
+        def recover_under_load(chunks, watch):
+            """one recovery of server 0 in `chunks` chunks, an update batch enqueued under every lock; with
+            `watch` the number of waiting updates is read back at every chunk (which waits for the stream)"""
             ctx.recovery_begin(0, chunks, buf_keys, buf_grads, per)
             torch.cuda.synchronize()
             tr0 = time.perf_counter()
@@ -559,30 +613,80 @@ def main():
                 done.record(side)
                 ctx.update(keys[ch % nb], grads[ch % nb])
                 main.wait_event(done)
-                waiting = max(waiting, ctx.recovery_state()["buffered"])
+                if watch:
+                    waiting = max(waiting, ctx.recovery_state()["buffered"])
                 ctx.recovery_unlock()
             torch.cuda.synchronize()
-            tr1 = time.perf_counter()
+            return time.perf_counter() - tr0, waiting
+
+        for chunks in (() if args.combine else (1, 10)):    # the protocol is defined for asynchronous training only
+            secs, _ = recover_under_load(chunks, False)      # timed: nothing in the loop waits for the device
             rc_status = ctx.status()
+            _, waiting = recover_under_load(chunks, True)    # once more, untimed, watching the buffer
+            rc_status = rc_status or ctx.status()
             under_load[str(chunks)] = {
-                "recovery_ms": (tr1 - tr0) * 1e3, "updates_applied_meanwhile": chunks * per,
-                "items_per_s_during_recovery": chunks * per / (tr1 - tr0),
-                "relative_to_normal": chunks * per / (tr1 - tr0) / value,
+                "recovery_ms": secs * 1e3, "updates_applied_meanwhile": chunks * per,
+                "items_per_s_during_recovery": chunks * per / secs,
+                "relative_to_normal": chunks * per / secs / value,
                 "max_updates_waiting": waiting, "status": rc_status}
             if rc_status != 0:
                 ctx.clear_status()
         out["recovery"]["under_load"] = under_load
         del buf_keys, buf_grads
 
+    # ---- what this device's memory delivers to the plainest kernels (context for the fractions above;
+    #      measured after the timed region, on memory of its own)
+    if not args.no_ceilings:
+        out["ceilings"] = memory_ceilings(torch, dev)
+
+    # ---- the same update with one plain allocation per array, as a caller who does not arrange the tables
+    #      would have it (the arena above is this benchmark's own arrangement)
+    if args.separate_figure and not args.graph and geometries[-1] not in ("separate", "probed"):
+        ctx.drop_buffers()
+        keep = min(nb, 2)
+        hk = [keys[b].clone() for b in range(keep)]
+        del E, A, PE, PA, ld, lp, scratch, keys, grads, arena
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        E, A = torch.empty(R, D, device=dev), torch.empty(R, D, device=dev)
+        PE, PA = torch.empty(R // k, D, device=dev), torch.empty(R // k, D, device=dev)
+        ld, lp = torch.zeros(S, dtype=torch.int64, device=dev), torch.zeros(S, dtype=torch.int64, device=dev)
+        scratch = torch.empty(sizes["scratch"], dtype=torch.uint8, device=dev)
+        keys = hk
+        grads = [torch.empty(per, D, device=dev) for _ in range(keep)]
+        ctx.bind(E, A, PE, PA, ld, lp, scratch)
+        fill_tables()
+        for b in range(keep):
+            for i0 in range(0, per, CH):
+                i1 = min(per, i0 + CH)
+                grads[b][i0:i1] = si.grads(seed, b * per + i0, i1 - i0, D, dev)
+        for b in range(keep):
+            ctx.update(keys[b], grads[b])
+        ctx.profile(True)
+        ctx.profile_read()
+        torch.cuda.synchronize()
+        ts0 = time.perf_counter()
+        reps = 6
+        for i in range(reps):
+            ctx.update(keys[i % keep], grads[i % keep])
+        torch.cuda.synchronize()
+        ts1 = time.perf_counter()
+        sms, scalls = ctx.profile_read()
+        ctx.profile(False)
+        assert ctx.status() == 0
+        sep_apply = sum(alg_apply[i % keep] for i in range(reps)) / (sms[2] * 1e-3) / 1e9
+        sep_path = sum(alg_path[i % keep] for i in range(reps)) / (ts1 - ts0) / 1e9
+        out["separate_allocations"] = {
+            "what": "one torch allocation per array, as they come; same kernels, same batches",
+            "ms_per_step": (ts1 - ts0) / reps * 1e3, "items_per_s": per * reps / (ts1 - ts0),
+            "apply_frac_of_hbm_peak": sep_apply / HBM_PEAK_GBS, "path_frac_of_hbm_peak": sep_path / HBM_PEAK_GBS}
+
     if not args.no_cpu_baseline:
         import oracle
         threads = min(16, oracle.max_threads())
         hld, hlp = np.zeros(S, np.uint64), np.zeros(S, np.uint64)
         cpu_items, cpu_s, nbatch = 0, 0.0, 0
-        for b in range(nb):
-            sel = torch.nonzero(keys[b] < shard_rows).squeeze(1)
-            hk = keys[b][sel].cpu().numpy().view(np.uint64)
-            hg = grads[b][sel].cpu().numpy()
+        for hk, hg in cpu_batches:
             tc = time.perf_counter()
             oracle.update(hE, hA, hPE, hPA, k, S, si.DEFAULT_LR, si.DEFAULT_EPS, hk, hg, hld, hlp, threads=threads)
             cpu_s += time.perf_counter() - tc
@@ -590,15 +694,30 @@ def main():
             nbatch += 1
             if cpu_s * threads > 20.0 or nbatch == 4:
                 break
-        n1 = min(len(hk), 1 << 16)                      # the same oracle on one thread, on a slice of that sample
+        # the same oracle on ONE thread, on the medium workload (2^22 updates on 2^20 rows): a 1/16 shard of
+        # its stripes with all their updates
+        wm = si.WORKLOADS["medium"]
+        mR = wm["R"] // k * k
+        m_rows = max(k, (mR // 16) // k * k)
+        mk = si.workload_keys_t("medium", 0, 0, dev)
+        mk = torch.where(mk >= mR, mk - mR, mk)
+        msel = torch.nonzero(mk < m_rows).squeeze(1)
+        mkeys = mk[msel].cpu().numpy().view(np.uint64)
+        mg = np.ascontiguousarray(si.grad_rows(wm["seed"], msel.cpu().numpy(), D))
+        mE = si.table(wm["seed"], si.TAG_E0, m_rows, D).numpy().copy()
+        mA = si.table(wm["seed"], si.TAG_A0, m_rows, D).numpy().copy()
+        mPE, mPA = oracle.encode(mE, k), oracle.encode(mA, k)
         tc = time.perf_counter()
-        oracle.update(hE, hA, hPE, hPA, k, S, si.DEFAULT_LR, si.DEFAULT_EPS, hk[:n1], hg[:n1], hld, hlp, threads=1)
+        oracle.update(mE, mA, mPE, mPA, k, S, si.DEFAULT_LR, si.DEFAULT_EPS, mkeys, mg, threads=1)
         one_s = time.perf_counter() - tc
         out["cpu_baseline"] = {"value": cpu_items / cpu_s, "unit": "items/s", "cores": threads, "kind": "oracle",
                                "sample": f"rows [0,{shard_rows}) (1/16 of the stripes) of the same tables and all "
                                          f"their updates from the first {nbatch} batches: {cpu_items} items, "
                                          f"{cpu_s:.2f}s wall",
-                               "single_thread_value": n1 / one_s, "host_cpus": os.cpu_count()}
+                               "single_thread_value": len(mkeys) / one_s,
+                               "single_thread_sample": f"medium workload, rows [0,{m_rows}) (1/16 of its stripes) with all "
+                                                       f"their updates: {len(mkeys)} items, {one_s:.2f}s wall",
+                               "host_cpus": os.cpu_count()}
     print(json.dumps(out), flush=True)
 
 

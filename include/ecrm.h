@@ -179,7 +179,11 @@ int ecrm_degraded_read(ecrm_ctx *ctx, const uint64_t *keys, uint64_t n, uint32_t
  *
  *   ecrm_recovery_begin   declares `server` lost (its rows are NOT overwritten; use ecrm_fail_server
  *                         in tests) and hands over the buffer: device memory for 2*capacity keys
- *                         (u64) and 2*capacity gradient rows, capacity <= max_batch.  EINVAL with
+ *                         (u64) and 2*capacity gradient rows, capacity <= max_batch = the largest number
+ *                         of updates that can wait at one time.  (The library keeps two lists of
+ *                         (key, row slot) entries in buf_keys, a pool of `capacity` gradient rows in the
+ *                         first half of buf_grads and its bookkeeping in the second half: a gradient row
+ *                         is copied once, when its update is first held back, however long it waits.)  EINVAL with
  *                         combine = 1: synchronous training takes one step per entry and training step,
  *                         and a buffer replayed in one go would merge the waiting updates of several
  *                         steps into one.
@@ -188,9 +192,10 @@ int ecrm_degraded_read(ecrm_ctx *ctx, const uint64_t *keys, uint64_t n, uint32_t
  *                         stream than the updates, provided it starts after every ecrm_update that was
  *                         enqueued BEFORE the lock has finished (an event from that stream).
  *   ecrm_recovery_unlock  call on the update stream once the decode has finished (wait for its event
- *                         first; ESTATE if no decode was enqueued under this lock).  SYNCHRONISES the stream to learn how many updates are waiting,
- *                         releases the chunk and enqueues the replay of the buffer (what must keep
- *                         waiting goes back into the buffer).  After the last chunk the recovery ends.
+ *                         first; ESTATE if no decode was enqueued under this lock).  Releases the chunk
+ *                         and enqueues the replay of the buffer (what must keep waiting stays in the
+ *                         buffer); like ecrm_update it only enqueues.  After the last chunk the
+ *                         recovery ends.
  *   ecrm_recovery_state   waits for the stream; reports whether a recovery is active, the number of
  *                         chunks rebuilt, the number of chunks, and how many updates are waiting.
  * A batch whose held-back items do not fit the buffer is rejected as a whole (sticky EBUFFER).
@@ -209,9 +214,9 @@ int ecrm_recovery_state(ecrm_ctx *ctx, void *hip_stream, uint32_t *active, uint3
  * entry keys[i] with its waiting updates applied in arrival order -- the value it will have once they
  * are replayed; an entry that the failed server held and that is not rebuilt yet is decoded from its
  * stripe first.  Nothing is modified, so the read may be repeated.  Call it on the update stream.
- * While a recovery is active the call SYNCHRONISES the stream (it has to learn how many updates are
- * waiting) and uses the scratch buffer to group them by entry; without one it is a plain gather and
- * only enqueues.  Keys >= rows raise the sticky EKEYRANGE status and leave their rows unwritten. */
+ * While a recovery is active the call uses the scratch buffer to group the waiting updates by entry
+ * (sized by the buffer's capacity: how many are waiting is read on the device); without one it is a plain
+ * gather.  Either way it only enqueues.  Keys >= rows raise the sticky EKEYRANGE status and leave their rows unwritten. */
 int ecrm_recovery_read(ecrm_ctx *ctx, const uint64_t *keys, uint64_t n, float *out_E, float *out_A,
                        void *hip_stream);
 

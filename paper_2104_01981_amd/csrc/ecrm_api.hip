@@ -42,9 +42,8 @@ struct ecrm_ctx {
     RecoveryView rv;
     uint32_t rec_chunks;
     bool rec_decoded;         // the locked chunk's reconstruction has been enqueued
-    unsigned long long *buf_keys[2];
-    float *buf_grads[2];
-    uint32_t buf_cap, buf_cur;
+    HoldBuffer hb;            // the caller's recovery buffer, carved
+    uint32_t buf_cur;         // which of its two lists is in use
     // profiling
     bool profiling;
     hipEvent_t ev[ECRM_PROFILE_MAX_CALLS][2 * ECRM_PHASES + 1];   // a call with gradient propagation has the phases twice
@@ -245,7 +244,7 @@ static int check_launch()
 static void init_if_needed(ecrm_ctx *c, hipStream_t st)
 {
     if (c->need_init) {
-        launch_reset(c->s, c->geo.S, 0, true, st);
+        launch_reset(c->s, c->geo.S, 0, true, kCallerBatch, st);
         c->need_init = false;
     }
 }
@@ -274,22 +273,24 @@ int ecrm_route(ecrm_ctx *c, const uint64_t *keys, uint64_t n, uint64_t *stripe, 
 // held-back items are appended to buf[target] (and the key space gets one more value, `rows`, for them
 // to sort behind the rest).
 static int run_update(ecrm_ctx *c, const Tables &t, const Scratch &s, const Layout &l, const RecoveryView &rv,
-                      bool clear_sticky, const uint64_t *keys, const float *grads, uint32_t n32, uint32_t target,
+                      bool clear_sticky, BatchSource src, const uint64_t *keys, const float *grads, uint32_t n32,
                       hipStream_t st)
 {
+    // a replay of the waiting updates: n32 only bounds their number, the kernels read the count on the device
+    const uint32_t *n_dev = src == kWaitingUpdates ? &s.hdr->n_batch : nullptr;
     hipEvent_t *ev = nullptr;
     if (c->profiling && c->ev_calls < ECRM_PROFILE_MAX_CALLS) ev = c->ev[c->ev_calls++];
 
-    launch_reset(s, c->geo.S, n32, clear_sticky, st);
+    launch_reset(s, c->geo.S, n32, clear_sticky, src, st);
     if (ev) (void)hipEventRecord(ev[0], st);
     int key_bits = c->key_bits;
     if (rv.active)
         while (key_bits < 32 && (1ull << key_bits) <= c->cfg.rows) ++key_bits;
     const uint32_t prop = c->cfg.propagation;
     uint32_t *sk = nullptr, *si = nullptr;
-    launch_sort(s, c->geo, rv, keys, n32, key_bits, false, true, &sk, &si, st);
-    if (rv.active)
-        launch_hold_back(s, c->geo, rv, keys, grads, n32, c->buf_keys[target], c->buf_grads[target], c->buf_cap, st);
+    launch_sort(s, c->geo, rv, keys, n32, n_dev, src, key_bits, false, true, &sk, &si, st);
+    if (rv.active || src == kWaitingUpdates)
+        launch_hold_back(s, c->geo, rv, keys, grads, n32, src, c->hb, c->buf_cur, st);
     if (ev) (void)hipEventRecord(ev[1], st);
     launch_chains(s, c->geo, c->lg, t.A, grads, sk, si, n32, l.max_slots, l.max_pieces, c->cus, st);
     if (ev) (void)hipEventRecord(ev[2], st);
@@ -306,8 +307,8 @@ static int run_update(ecrm_ctx *c, const Tables &t, const Scratch &s, const Layo
         int bits = 1;
         while (bits < 32 && (1ull << bits) < c->cfg.rows / c->cfg.k) ++bits;
         if (ev) (void)hipEventRecord(ev[3], st);
-        launch_reset(s, c->geo.S, n32, false, st);
-        launch_sort(s, c->geo, rv, keys, n32, bits, true, false, &sk, &si, st);
+        launch_reset(s, c->geo.S, n32, false, kCallerBatch, st);
+        launch_sort(s, c->geo, rv, keys, n32, nullptr, kCallerBatch, bits, true, false, &sk, &si, st);
         if (ev) (void)hipEventRecord(ev[4], st);
         launch_chains(s, gp, c->lg, t.PA, grads, sk, si, n32, l.max_slots, l.max_pieces, c->cus, st);
         if (ev) (void)hipEventRecord(ev[5], st);
@@ -319,12 +320,12 @@ static int run_update(ecrm_ctx *c, const Tables &t, const Scratch &s, const Layo
     return check_launch();
 }
 
-static int run_bound_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uint32_t n32, uint32_t target,
+static int run_bound_update(ecrm_ctx *c, BatchSource src, const uint64_t *keys, const float *grads, uint32_t n32,
                             hipStream_t st)
 {
     const bool clear = c->need_init;
     c->need_init = false;
-    return run_update(c, c->t, c->s, c->lay, c->rv, clear, keys, grads, n32, target, st);
+    return run_update(c, c->t, c->s, c->lay, c->rv, clear, src, keys, grads, n32, st);
 }
 
 int ecrm_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uint64_t n, void *stream)
@@ -334,7 +335,7 @@ int ecrm_update(ecrm_ctx *c, const uint64_t *keys, const float *grads, uint64_t 
     if (n > c->lay.max_batch) return ECRM_EBATCH;
     if (n == 0) return ECRM_OK;
     if (!aligned(keys, 8) || !aligned(grads, 16)) return ECRM_EINVAL;
-    return run_bound_update(c, keys, grads, (uint32_t)n, c->buf_cur, (hipStream_t)stream);
+    return run_bound_update(c, kCallerBatch, keys, grads, (uint32_t)n, (hipStream_t)stream);
 }
 
 // ---- ecrm_update for callers that cannot provide a scratch buffer --------------------------------
@@ -400,7 +401,7 @@ int ecrm_update_static(ecrm_ctx *c, float *E, float *A, float *PE, float *PA, ui
     memset(&none, 0, sizeof(none));
     // the array keeps the last call's contents: the reset kernel clears every field of the header,
     // the per-server counts and (clear_sticky) the status word; everything else is written before it is read
-    rc = run_update(c, t, s, c->slay, none, true, keys, grads, (uint32_t)n, 0, st);
+    rc = run_update(c, t, s, c->slay, none, true, kCallerBatch, keys, grads, (uint32_t)n, st);
     if (rc == ECRM_OK && rejected) {
         hipLaunchKernelGGL(publish_rejected_kernel, dim3(1), dim3(64), 0, st, s.hdr, rejected);
         rc = check_launch();
@@ -431,14 +432,16 @@ int ecrm_recovery_begin(ecrm_ctx *c, uint32_t server, uint32_t chunks, uint64_t 
     c->rv.stripes_per_chunk = spc;
     c->rv.dspc = spc_div;
     c->rec_chunks = (uint32_t)(((uint64_t)stripes + spc - 1) / spc);
-    c->buf_cap = (uint32_t)capacity;
+    // The caller's buffer: two lists of `capacity` entries (key and row-pool slot in 64 bits); a pool of
+    // `capacity` gradient rows; and, in the memory behind the pool, the released slots.
+    c->hb.cap = (uint32_t)capacity;
+    c->hb.list[0] = (unsigned long long *)buf_keys;
+    c->hb.list[1] = (unsigned long long *)buf_keys + capacity;
+    c->hb.rows = buf_grads;
+    c->hb.free_list = (uint32_t *)(buf_grads + capacity * c->geo.D);
     c->buf_cur = 0;
-    c->buf_keys[0] = (unsigned long long *)buf_keys;
-    c->buf_keys[1] = (unsigned long long *)buf_keys + capacity;
-    c->buf_grads[0] = buf_grads;
-    c->buf_grads[1] = buf_grads + capacity * c->geo.D;
     init_if_needed(c, (hipStream_t)stream);
-    launch_set_buf_count(c->s, 0, (hipStream_t)stream);
+    launch_clear_buffer(c->s, (hipStream_t)stream);
     return check_launch();
 }
 
@@ -458,7 +461,9 @@ int ecrm_recovery_decode(ecrm_ctx *c, void *stream)
     const uint64_t stripes = c->geo.rows / c->geo.k;
     const uint64_t lo = (uint64_t)c->rv.next * c->rv.stripes_per_chunk;
     const uint64_t hi = lo + c->rv.stripes_per_chunk < stripes ? lo + c->rv.stripes_per_chunk : stripes;
-    launch_recover_range(c->geo, c->t.E, c->t.A, c->t.PE, c->t.PA, c->rv.server, (uint32_t)lo, (uint32_t)hi, c->grid_blocks,
+    // a grid sized to the chunk, not a resident one: the decoder is meant to run beside the updates of
+    // another stream, which must be able to get onto the device while it runs
+    launch_recover_range(c->geo, c->t.E, c->t.A, c->t.PE, c->t.PA, c->rv.server, (uint32_t)lo, (uint32_t)hi, 0,
                          (hipStream_t)stream);
     const int rc = check_launch();
     if (rc == ECRM_OK) c->rec_decoded = true;
@@ -470,19 +475,14 @@ int ecrm_recovery_unlock(ecrm_ctx *c, void *stream)
     if (!c) return ECRM_EINVAL;
     if (!c->rv.active || !c->rv.locked || !c->rec_decoded) return ECRM_ESTATE;   // nothing rebuilt: lost rows would be trained on
     hipStream_t st = (hipStream_t)stream;
-    // how much is waiting: the only synchronisation of the recovery protocol
-    if (hipStreamSynchronize(st) != hipSuccess) return ECRM_EHIP;
-    Header h;
-    if (hipMemcpy(&h, c->s.hdr, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return ECRM_EHIP;
     c->rv.locked = 0;
     c->rv.next += 1;
-    const uint32_t waiting = h.buf_count;
-    const uint32_t src = c->buf_cur;
-    c->buf_cur ^= 1u;                               // what still has to wait is re-appended to the other half
-    launch_set_buf_count(c->s, 0, st);
-    int rc = check_launch();
-    if (rc == ECRM_OK && waiting)
-        rc = run_bound_update(c, (const uint64_t *)c->buf_keys[src], c->buf_grads[src], waiting, c->buf_cur, st);
+    // Replay of everything that is waiting, under the new state of the recovery: what the released chunk
+    // held is applied, what must go on waiting moves to the other list (its gradient row stays where it
+    // is).  How many updates are waiting is known on the device only: the launches are sized by the
+    // buffer's capacity and the kernels read the count there -- nothing here waits for the stream.
+    const int rc = run_bound_update(c, kWaitingUpdates, (const uint64_t *)c->hb.list[c->buf_cur], c->hb.rows, c->hb.cap, st);
+    c->buf_cur ^= 1u;
     if (c->rv.next >= c->rec_chunks) c->rv.active = 0;       // every chunk is rebuilt, nothing can be waiting any more
     return rc;
 }
@@ -516,19 +516,15 @@ int ecrm_recovery_read(ecrm_ctx *c, const uint64_t *keys, uint64_t n, float *out
                              c->grid_blocks, st);
         return check_launch();
     }
-    // how many updates are waiting (the grouping below is sized by it)
-    if (hipStreamSynchronize(st) != hipSuccess) return ECRM_EHIP;
-    Header h;
-    if (hipMemcpy(&h, c->s.hdr, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return ECRM_EHIP;
-    const uint32_t m = h.buf_count;
+    // The waiting updates, grouped by entry with the update path's own sort on the list's keys.  How
+    // many there are is known on the device only: the launches are sized by the buffer's capacity.
     uint32_t *bk = nullptr, *bi = nullptr;
-    if (m) {
-        RecoveryView none;
-        memset(&none, 0, sizeof(none));
-        launch_sort(c->s, c->geo, none, (const uint64_t *)c->buf_keys[c->buf_cur], m, c->key_bits, false, false, &bk, &bi, st);
-    }
-    launch_recovery_read(c->s, c->geo, c->rv, c->t.E, c->t.A, c->t.PE, c->t.PA, keys, n, bk, bi, m, c->buf_grads[c->buf_cur],
-                         out_E, out_A, c->grid_blocks, st);
+    RecoveryView none;
+    memset(&none, 0, sizeof(none));
+    launch_sort(c->s, c->geo, none, (const uint64_t *)c->hb.list[c->buf_cur], c->hb.cap, &c->s.hdr->buf_count, kWaitingUpdates,
+                c->key_bits, false, false, &bk, &bi, st);
+    launch_recovery_read(c->s, c->geo, c->rv, c->t.E, c->t.A, c->t.PE, c->t.PA, keys, n, bk, bi, &c->s.hdr->buf_count,
+                         c->hb.rows, out_E, out_A, c->grid_blocks, st);
     return check_launch();
 }
 

@@ -44,7 +44,11 @@ struct Header {
     uint32_t n_held;       // items of the batch held back
     uint32_t buf_count;    // held-back items waiting in the buffer (all batches)
     uint32_t apply_ticket; // next group of sorted positions the apply kernel hands out (cleared by reset)
-    uint32_t pad[54];
+    uint32_t n_batch;      // items of the batch in flight: the caller's n, or -- when the waiting updates are
+                           // replayed -- what buf_count was when the replay started (set by reset)
+    uint32_t free_count;   // slots of the recovery buffer's row pool that were released and can be reused
+    uint32_t bump;         // slots of the row pool that have ever been handed out
+    uint32_t pad[51];
 };
 static_assert(sizeof(Header) == 256, "header is one 256-byte block");
 
@@ -150,16 +154,29 @@ struct LaunchGrids {
 bool query_launch_grids(const Geometry &g, int cus, LaunchGrids *out);   // false: an occupancy query failed
 
 // ---- launchers (each checks nothing: the API layer validates shapes before calling) -------------
-void launch_reset(const Scratch &s, uint32_t S, uint32_t n, bool clear_sticky, hipStream_t st);
+// Where a batch comes from.  kCallerBatch: n keys of the caller with gradient row i for item i.
+// kWaitingUpdates: the entries of the recovery buffer's list -- (key, row-pool slot) packed into 64 bits --
+// of which only the device knows how many there are (n is then an upper bound that sizes the grids).
+enum BatchSource { kCallerBatch = 0, kWaitingUpdates = 1 };
+// The buffer of a recovery in progress (Sec. 3.4): a pool of gradient rows addressed by slot, two lists
+// of waiting updates (the one in use and the one the next replay builds), and the released slots.
+struct HoldBuffer {
+    unsigned long long *list[2];   // [cap] each: key | slot << 32, in arrival order
+    float *rows;                   // [cap][D]
+    uint32_t *free_list;           // [cap]
+    uint32_t cap;
+};
+void launch_reset(const Scratch &s, uint32_t S, uint32_t n, bool clear_sticky, BatchSource src, hipStream_t st);
+// n_dev (may be null): device word holding the true item count when n is only its upper bound
 void launch_sort(const Scratch &s, const Geometry &g, const RecoveryView &rv, const uint64_t *keys, uint32_t n,
-                 int key_bits, bool by_stripe, bool count_servers, uint32_t **sorted_keys,
-                 uint32_t **sorted_vals, hipStream_t st);
+                 const uint32_t *n_dev, BatchSource src, int key_bits, bool by_stripe, bool count_servers,
+                 uint32_t **sorted_keys, uint32_t **sorted_vals, hipStream_t st);
 void launch_hold_back(const Scratch &s, const Geometry &g, const RecoveryView &rv, const uint64_t *keys,
-                      const float *grads, uint32_t n, unsigned long long *buf_keys, float *buf_grads,
-                      uint32_t buf_cap, hipStream_t st);
+                      const float *grads, uint32_t n, BatchSource src, const HoldBuffer &hb, uint32_t cur,
+                      hipStream_t st);
 void launch_recover_range(const Geometry &g, float *E, float *A, float *PE, float *PA, uint32_t server,
                           uint32_t g_lo, uint32_t g_hi, int grid_blocks, hipStream_t st);
-void launch_set_buf_count(const Scratch &s, uint32_t count, hipStream_t st);
+void launch_clear_buffer(const Scratch &s, hipStream_t st);
 void launch_chains(const Scratch &s, const Geometry &g, const LaunchGrids &lg, const float *A, const float *grads,
                    const uint32_t *sk, const uint32_t *si, uint32_t n, uint32_t max_slots,
                    uint32_t max_pieces, int cus, hipStream_t st);
@@ -172,7 +189,7 @@ void launch_route(const Scratch &s, const Geometry &g, const uint64_t *keys, uin
                   uint32_t *member, uint32_t *data_srv, uint32_t *parity_srv, hipStream_t st);
 void launch_recovery_read(const Scratch &s, const Geometry &g, const RecoveryView &rv, const float *E, const float *A,
                           const float *PE, const float *PA, const uint64_t *keys, uint64_t n, const uint32_t *bk,
-                          const uint32_t *bi, uint32_t m, const float *buf_grads, float *out_E, float *out_A,
+                          const uint32_t *bi, const uint32_t *m_dev, const float *buf_grads, float *out_E, float *out_A,
                           int grid_blocks, hipStream_t st);
 void launch_clear_status(const Scratch &s, hipStream_t st);
 void launch_fail_server(const Geometry &g, float *E, float *A, float *PE, float *PA, uint32_t server,

@@ -79,12 +79,22 @@ __device__ __forceinline__ void rebuild_row(float *T, float *P, uint32_t g, int 
     }
 }
 
-// stripes [g_lo, g_hi)
+// stripes [g_lo, g_hi).  per_wave == 0: the waves of a resident grid stride over the range (a recovery
+// that has the device to itself).  per_wave > 0: wave w takes stripes g_lo + w * per_wave ... of a grid
+// sized to the range, so that workgroups retire all the time and the kernels of another stream -- the
+// updates that go on during a recovery, Sec. 3.4 -- get their share of the device.
 __global__ __launch_bounds__(256) void recover_server_kernel(float *E, float *A, float *PE, float *PA, uint32_t g_lo,
-                                                             uint32_t g_hi, uint32_t D, uint32_t k, uint32_t S, uint32_t server)
+                                                             uint32_t g_hi, uint32_t D, uint32_t k, uint32_t S, uint32_t server,
+                                                             uint32_t per_wave)
 {
-    const uint64_t w0 = (blockIdx.x * blockDim.x + threadIdx.x) / kWave, nw = (gridDim.x * blockDim.x) / kWave;
-    for (uint64_t g64 = (uint64_t)g_lo + w0; g64 < g_hi; g64 += nw) {
+    const uint64_t w0 = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave, nw = ((uint64_t)gridDim.x * blockDim.x) / kWave;
+    uint64_t first = (uint64_t)g_lo + w0, last = g_hi, step = nw;
+    if (per_wave) {
+        first = (uint64_t)g_lo + w0 * per_wave;
+        last = first + per_wave < (uint64_t)g_hi ? first + per_wave : (uint64_t)g_hi;
+        step = 1;
+    }
+    for (uint64_t g64 = first; g64 < last; g64 += step) {
         const uint32_t g = (uint32_t)g64;
         const int u = unit_on_server(g, k, S, server);
         if (u < 0) continue;
@@ -167,12 +177,24 @@ void launch_recover_server(const Geometry &g, float *E, float *A, float *PE, flo
     launch_recover_range(g, E, A, PE, PA, server, 0, g.rows / g.k, grid_blocks, st);
 }
 
+// grid_blocks > 0: a resident grid of that many workgroups; 0: a grid sized to the range (see the kernel)
 void launch_recover_range(const Geometry &g, float *E, float *A, float *PE, float *PA, uint32_t server,
                           uint32_t g_lo, uint32_t g_hi, int grid_blocks, hipStream_t st)
 {
     if (g_lo >= g_hi) return;
+    uint32_t per_wave = 0;
+    if (grid_blocks <= 0) {
+        constexpr uint32_t kWavesPerBlock = 256 / kWave;
+        per_wave = 16;
+        uint64_t blocks = ((uint64_t)(g_hi - g_lo) + per_wave * kWavesPerBlock - 1) / (per_wave * kWavesPerBlock);
+        while (blocks > (1u << 24)) {                  // keep the grid moderate for the very largest tables
+            per_wave *= 2;
+            blocks = ((uint64_t)(g_hi - g_lo) + per_wave * kWavesPerBlock - 1) / (per_wave * kWavesPerBlock);
+        }
+        grid_blocks = (int)blocks;
+    }
     hipLaunchKernelGGL(recover_server_kernel, dim3(grid_blocks), dim3(256), 0, st, E, A, PE, PA, g_lo, g_hi, g.D, g.k, g.S,
-                       server);
+                       server, per_wave);
 }
 
 void launch_degraded_read(const Scratch &s, const Geometry &g, const float *E, const float *A, const float *PE,

@@ -43,21 +43,25 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *s_wave
     return off + incl - v;
 }
 
-__global__ void reset_kernel(Header *h, unsigned long long *cnt, uint32_t S, uint32_t n, int clear_sticky)
+__global__ void reset_kernel(Header *h, unsigned long long *cnt, uint32_t S, uint32_t n, int clear_sticky, int from_buffer)
 {
     const uint32_t t = threadIdx.x;
     if (t == 0) {
+        if (clear_sticky) {
+            h->err_sticky = 0;
+            h->buf_count = 0;
+            h->free_count = 0;
+            h->bump = 0;
+        }
+        if (from_buffer) n = min(n, h->buf_count);     // a replay: everything that is waiting right now
         h->batch_bad = 0;
         h->n_long = 0;
         h->n_pieces = 0;
         h->n_long_items = 0;
+        h->n_batch = n;
         h->n_valid = n;
         h->n_held = 0;
         h->apply_ticket = 0;
-        if (clear_sticky) {
-            h->err_sticky = 0;
-            h->buf_count = 0;
-        }
     }
     for (uint32_t i = t; i < 2 * S; i += blockDim.x) cnt[i] = 0;
 }
@@ -67,9 +71,13 @@ __global__ void clear_status_kernel(Header *h)
     if (threadIdx.x == 0) h->err_sticky = 0;
 }
 
-__global__ void set_buf_count_kernel(Header *h, uint32_t count)
+__global__ void clear_buffer_kernel(Header *h)
 {
-    if (threadIdx.x == 0) h->buf_count = count;
+    if (threadIdx.x == 0) {
+        h->buf_count = 0;
+        h->free_count = 0;
+        h->bump = 0;
+    }
 }
 
 // Tile a block works on.  Workgroups go to the 8 XCDs (each with its own L2) round-robin by block id;
@@ -92,10 +100,10 @@ __device__ __forceinline__ uint32_t tile_of_block(uint32_t b, uint32_t nblocks)
 // Sort key of one caller key in the first pass, the same in the histogram and in the scatter:
 // out-of-range keys keep their low bits (the batch is rejected anyway), held-back items get `rows`.
 __device__ __forceinline__ uint32_t first_pass_key(uint64_t k64, uint32_t rows, const Divider &dk, const Divider &dS,
-                                                   const RecoveryView &rv, bool by_stripe, bool &bad, bool &held)
+                                                   const RecoveryView &rv, bool by_stripe, bool packed, bool &bad, bool &held)
 {
     const uint32_t key = (uint32_t)k64;
-    bad = k64 >= (uint64_t)rows;
+    bad = !packed && k64 >= (uint64_t)rows;           // a waiting update's key was checked when it arrived
     held = !bad && held_back(rv, key, dk, dS);
     if (held) return rows;
     return by_stripe ? dk.div(key) : key;
@@ -106,11 +114,12 @@ __device__ __forceinline__ uint32_t first_pass_key(uint64_t k64, uint32_t rows, 
 // groups by row id / k instead (for the parity half of gradient propagation).
 template <bool FIRST>
 __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
-    const void *keys_in, uint32_t n, uint32_t nblocks, int shift, int bits, uint32_t *block_hist,
+    const void *keys_in, uint32_t n, const uint32_t *n_dev, uint32_t nblocks, int shift, int bits, uint32_t *block_hist,
     Header *hdr, unsigned long long *cnt, uint32_t rows, Divider dk, Divider dS, uint32_t count, RecoveryView rv,
-    uint32_t by_stripe)
+    uint32_t by_stripe, uint32_t packed)
 {
     __shared__ uint32_t s_hist[kMaxBins];
+    if (n_dev) n = min(n, *n_dev);
     __shared__ uint32_t s_cnt[2 * 1024];
     __shared__ uint32_t s_bad;
     const uint32_t tid = threadIdx.x;
@@ -133,7 +142,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
             if (FIRST) {
                 const uint64_t k64 = ((const uint64_t *)keys_in)[i];
                 bool oob, held;                                   // held back: sorts behind every row, not applied
-                key = first_pass_key(k64, rows, dk, dS, rv, by_stripe != 0, oob, held);
+                key = first_pass_key(k64, rows, dk, dS, rv, by_stripe != 0, packed != 0, oob, held);
                 bad |= oob;
                 if (!oob && !held && S) {
                     const uint32_t x = (uint32_t)k64, g = dk.div(x), j = x - g * dk.d;
@@ -184,8 +193,8 @@ __global__ __launch_bounds__(kSortThreads) void sort_scan_kernel(uint32_t *block
 template <bool FIRST>
 __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_kernel(
     const void *keys_in, const uint32_t *vals_in, uint32_t *keys_out, uint32_t *vals_out,
-    const uint32_t *block_hist, const uint32_t *bin_total, uint32_t n, uint32_t nblocks, int shift, int bits,
-    uint32_t rows, Divider dk, Divider dS, RecoveryView rv, uint32_t by_stripe)
+    const uint32_t *block_hist, const uint32_t *bin_total, uint32_t n, const uint32_t *n_dev, uint32_t nblocks, int shift,
+    int bits, uint32_t rows, Divider dk, Divider dS, RecoveryView rv, uint32_t by_stripe, uint32_t packed)
 {
     __shared__ uint32_t s_keys[kSortTile];
     __shared__ uint32_t s_vals[kSortTile];
@@ -196,6 +205,7 @@ __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_ke
 
     const uint32_t tid = threadIdx.x, wave = tid / kWave, lane = lane_id();
     const uint32_t bins = 1u << bits, mask = bins - 1;
+    if (n_dev) n = min(n, *n_dev);
     for (uint32_t i = tid; i < kSortWaves * kMaxBins; i += kSortThreads) (&s_wcnt[0][0])[i] = 0;
     __syncthreads();
 
@@ -209,8 +219,9 @@ __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_ke
         if (i < n) {
             if (FIRST) {
                 bool oob, held;
-                key[r] = first_pass_key(((const uint64_t *)keys_in)[i], rows, dk, dS, rv, by_stripe != 0, oob, held);
-                val[r] = i;
+                const uint64_t k64 = ((const uint64_t *)keys_in)[i];
+                key[r] = first_pass_key(k64, rows, dk, dS, rv, by_stripe != 0, packed != 0, oob, held);
+                val[r] = packed ? (uint32_t)(k64 >> 32) : i;        // where the item's gradient row is: slot, or item index
             } else {
                 key[r] = ((const uint32_t *)keys_in)[i];
                 val[r] = vals_in[i];
@@ -274,7 +285,7 @@ __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_ke
     }
     __syncthreads();
 
-    const uint32_t count = min((uint32_t)kSortTile, n - tile0);
+    const uint32_t count = tile0 < n ? min((uint32_t)kSortTile, n - tile0) : 0u;
     for (uint32_t i = tid; i < count; i += kSortThreads) {
         const uint32_t kk = s_keys[i];
         const uint32_t gpos = s_gbase[(kk >> shift) & mask] + i;
@@ -284,14 +295,15 @@ __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_ke
 }
 
 // ---- host side -------------------------------------------------------------------------------------
-void launch_reset(const Scratch &s, uint32_t S, uint32_t n, bool clear_sticky, hipStream_t st)
+void launch_reset(const Scratch &s, uint32_t S, uint32_t n, bool clear_sticky, BatchSource src, hipStream_t st)
 {
-    hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, st, s.hdr, s.cnt, S, n, clear_sticky ? 1 : 0);
+    hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(256), 0, st, s.hdr, s.cnt, S, n, clear_sticky ? 1 : 0,
+                       src == kWaitingUpdates ? 1 : 0);
 }
 
-void launch_set_buf_count(const Scratch &s, uint32_t count, hipStream_t st)
+void launch_clear_buffer(const Scratch &s, hipStream_t st)
 {
-    hipLaunchKernelGGL(set_buf_count_kernel, dim3(1), dim3(64), 0, st, s.hdr, count);
+    hipLaunchKernelGGL(clear_buffer_kernel, dim3(1), dim3(64), 0, st, s.hdr);
 }
 
 void launch_clear_status(const Scratch &s, hipStream_t st)
@@ -300,10 +312,11 @@ void launch_clear_status(const Scratch &s, hipStream_t st)
 }
 
 void launch_sort(const Scratch &s, const Geometry &g, const RecoveryView &rv, const uint64_t *keys, uint32_t n,
-                 int key_bits, bool by_stripe, bool count_servers, uint32_t **sorted_keys,
-                 uint32_t **sorted_vals, hipStream_t st)
+                 const uint32_t *n_dev, BatchSource src, int key_bits, bool by_stripe, bool count_servers,
+                 uint32_t **sorted_keys, uint32_t **sorted_vals, hipStream_t st)
 {
     const uint32_t count = (count_servers && !(g.mode & 2u)) ? 1u : 0u, bs = by_stripe ? 1u : 0u;
+    const uint32_t packed = src == kWaitingUpdates ? 1u : 0u;
     const uint32_t nblocks = (n + kSortTile - 1) / kSortTile;
     int passes = (key_bits + kMaxRadixBits - 1) / kMaxRadixBits;
     if (passes < 1) passes = 1;
@@ -316,23 +329,23 @@ void launch_sort(const Scratch &s, const Geometry &g, const RecoveryView &rv, co
         const uint32_t bins = 1u << bits;
         if (p == 0) {
             hipLaunchKernelGGL(sort_hist_kernel<true>, dim3(nblocks), dim3(kSortThreads), 0, st,
-                               (const void *)keys, n, nblocks, shift, bits, s.block_hist, s.hdr, s.cnt,
-                               g.rows, g.dk, g.dS, count, rv, bs);
+                               (const void *)keys, n, n_dev, nblocks, shift, bits, s.block_hist, s.hdr, s.cnt,
+                               g.rows, g.dk, g.dS, count, rv, bs, packed);
             hipLaunchKernelGGL(sort_scan_kernel, dim3(bins), dim3(kSortThreads), 0, st, s.block_hist,
                                s.bin_total, nblocks);
             hipLaunchKernelGGL(sort_scatter_kernel<true>, dim3(nblocks), dim3(kSortThreads), 0, st,
                                (const void *)keys, (const uint32_t *)nullptr, s.keys[0], s.vals[0],
-                               s.block_hist, s.bin_total, n, nblocks, shift, bits, g.rows, g.dk, g.dS, rv, bs);
+                               s.block_hist, s.bin_total, n, n_dev, nblocks, shift, bits, g.rows, g.dk, g.dS, rv, bs, packed);
             cur = 0;
         } else {
             hipLaunchKernelGGL(sort_hist_kernel<false>, dim3(nblocks), dim3(kSortThreads), 0, st,
-                               (const void *)s.keys[cur], n, nblocks, shift, bits, s.block_hist, s.hdr,
-                               s.cnt, g.rows, g.dk, g.dS, 0u, rv, 0u);
+                               (const void *)s.keys[cur], n, n_dev, nblocks, shift, bits, s.block_hist, s.hdr,
+                               s.cnt, g.rows, g.dk, g.dS, 0u, rv, 0u, 0u);
             hipLaunchKernelGGL(sort_scan_kernel, dim3(bins), dim3(kSortThreads), 0, st, s.block_hist,
                                s.bin_total, nblocks);
             hipLaunchKernelGGL(sort_scatter_kernel<false>, dim3(nblocks), dim3(kSortThreads), 0, st,
                                (const void *)s.keys[cur], s.vals[cur], s.keys[cur ^ 1], s.vals[cur ^ 1],
-                               s.block_hist, s.bin_total, n, nblocks, shift, bits, g.rows, g.dk, g.dS, rv, 0u);
+                               s.block_hist, s.bin_total, n, n_dev, nblocks, shift, bits, g.rows, g.dk, g.dS, rv, 0u, 0u);
             cur ^= 1;
         }
         shift += bits;

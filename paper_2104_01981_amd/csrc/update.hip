@@ -938,7 +938,7 @@ struct ReadArgs {
     const uint64_t *keys;
     uint64_t n;
     const uint32_t *bk, *bi;
-    uint32_t m;
+    const uint32_t *m_dev;   // how many updates are waiting (device word)
     const float *buf_grads;
     float *out_E, *out_A;
     Header *hdr;
@@ -952,6 +952,7 @@ __global__ __launch_bounds__(256) void recovery_read_kernel(ReadArgs a)
     const uint32_t D = a.geo.D, k = a.geo.k, S = a.geo.S, lane = lane_id();
     const RuleParams rp = rule_params(a.geo);
     const uint64_t nw = wave_count();
+    const uint32_t m = uniform(*a.m_dev);
     for (uint64_t i = wave_id(); i < a.n; i += nw) {
         const uint64_t key = a.keys[i];
         const uint32_t khi = uniform((uint32_t)(key >> 32)), x = uniform((uint32_t)key);
@@ -968,9 +969,9 @@ __global__ __launch_bounds__(256) void recovery_read_kernel(ReadArgs a)
                 decode = lost == j && g / a.rv.stripes_per_chunk >= a.rv.next;
             }
         }
-        uint32_t lo = a.m;                        // first waiting update of x, if it can have any
-        if (a.m && held_back(a.rv, x, a.geo.dk, a.geo.dS)) {
-            uint32_t l = 0, h = a.m;
+        uint32_t lo = m;                          // first waiting update of x, if it can have any
+        if (m && held_back(a.rv, x, a.geo.dk, a.geo.dS)) {
+            uint32_t l = 0, h = m;
             while (l < h) {
                 const uint32_t mid = l + (h - l) / 2;
                 if (uniform(a.bk[mid]) < x) l = mid + 1; else h = mid;
@@ -997,7 +998,7 @@ __global__ __launch_bounds__(256) void recovery_read_kernel(ReadArgs a)
             }
             D2 G = start2<MODE>(s0), acc = D2{0, 0};
             bool any = false;
-            for (uint32_t pos = lo; pos < a.m; ++pos) {
+            for (uint32_t pos = lo; pos < m; ++pos) {
                 if (uniform(a.bk[pos]) != x) break;
                 const float2 gr = ld2<0>(row_f32(a.buf_grads, uniform(a.bi[pos]), D, col0), 0);
                 item2<MODE>(G, acc, gr, rp);
@@ -1157,12 +1158,12 @@ void launch_apply(const Scratch &s, const Geometry &g, const LaunchGrids &lg, fl
 
 void launch_recovery_read(const Scratch &s, const Geometry &g, const RecoveryView &rv, const float *E, const float *A,
                           const float *PE, const float *PA, const uint64_t *keys, uint64_t n, const uint32_t *bk,
-                          const uint32_t *bi, uint32_t m, const float *buf_grads, float *out_E, float *out_A,
+                          const uint32_t *bi, const uint32_t *m_dev, const float *buf_grads, float *out_E, float *out_A,
                           int grid_blocks, hipStream_t st)
 {
     ReadArgs a;
     a.E = E; a.A = A; a.PE = PE; a.PA = PA;
-    a.keys = keys; a.n = n; a.bk = bk; a.bi = bi; a.m = m; a.buf_grads = buf_grads;
+    a.keys = keys; a.n = n; a.bk = bk; a.bi = bi; a.m_dev = m_dev; a.buf_grads = buf_grads;
     a.out_E = out_E; a.out_A = out_A; a.hdr = s.hdr; a.rv = rv; a.geo = g;
     const dim3 grid(grid_blocks), block(256);
     switch (g.mode) {
