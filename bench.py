@@ -125,10 +125,9 @@ def main():
     ap.add_argument("--separate-figure", type=int, default=-1,
                     help="1: after the main measurement, measure the same update with one plain allocation per array "
                          "and report it beside the arena's figure (default: on for the large workloads)")
-    ap.add_argument("--layout", default="auto", choices=["auto", "probed", "arena", "separate"],
+    ap.add_argument("--layout", default="auto", choices=["auto", "arena", "separate"],
                     help="auto: the built-in list of layouts, one per placement trial; arena: one arena in --order; "
-                         "probed: one allocation per array, each kept only if a random-row read probe finds it in "
-                         "the fast part of the device memory; separate: one torch allocation per array as it comes")
+                         "separate: one torch allocation per array as it comes")
     ap.add_argument("--placement-trials", type=int, default=4,
                     help="how many arenas to try at most when the placement probe is slow")
     ap.add_argument("--fresh-process-retry", type=int, default=1,
@@ -218,11 +217,7 @@ def main():
     GEOMETRIES = ["E,g0,g1,A,g2,g3,PE,PA,scratch,keys,g*",
                   "pad16,E,g0,g1,A,g2,g3,PE,PA,scratch,keys,g*",
                   "E,g0,g1,g2,g3,A,g4,g5,g6,g7,PE,PA,scratch,keys,g*",
-                  "probed",
-                  "pad8,E,g0,g1,A,g2,g3,PE,PA,scratch,keys,g*",
-                  "E,g0,g1,g2,g3,g4,g5,A,g6,g7,g8,g9,g10,g11,PE,g12,PA,scratch,keys,g*",
-                  "pad64,E,g0,g1,A,g2,g3,PE,PA,scratch,keys,g*",
-                  "probed"]
+                  "separate"]
 
     def geometry(spec):
         """offsets of the resident arrays inside one arena, and its size"""
@@ -280,106 +275,19 @@ def main():
                     2 * per * 8 + (2 * per - n_long - n_long_p) * 4 * D + (U + Up) * 16 * D)
         return per * (8 + 4 * D) + (U + Up) * 16 * D, per * 8 + (per - n_long) * 4 * D + (U + Up) * 16 * D
 
-    # Physical placement is the driver's; now and then (e.g. right after another process released a
-    # lot of memory) the same virtual layout lands badly and every kernel that sweeps the tables runs
-    # ~15 % slower for the life of the allocation.  Probe with three updates of batch 0 and, if the
-    # apply kernel is clearly off its usual rate, release the memory and take the next geometry.
-    #
-    # One ingredient (measured with plain torch gathers, no kernel of this library): about 30 % of the
-    # device memory -- which part differs from process to process -- serves random 512-byte row reads
-    # 8-9 % slower than the rest (3.7 vs 4.05 TB/s for index_select), while sequential copies run at
-    # the same rate everywhere.  The "probed" layout allocates every array on its own, probes the
-    # block with such a gather, and keeps it only if it is in the fast part (a block that is not is
-    # held aside until all arrays are placed, so that the driver hands out other memory).  It is one
-    # of the layouts tried, not the first: separate allocations land at distances from each other
-    # that are often bad in the other respect (0.63-0.75).
-    probe_log = {}
-
-    def row_probe(block, out, idx):
-        nrows = block.numel() // 512
-        v = block[:nrows * 512].view(torch.float32).view(nrows, 128)
-        ii = idx % nrows
-        torch.index_select(v, 0, ii, out=out)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(3):
-            torch.index_select(v, 0, ii, out=out)
-        e1.record()
-        torch.cuda.synchronize()
-        return 3 * 2 * idx.numel() * 512 / e0.elapsed_time(e1) / 1e6      # GB/s, read + write
-
-    def alloc_probed():
-        gen = torch.Generator(device=dev)
-        gen.manual_seed(12345)
-        idx = torch.randint(0, 1 << 40, (1 << 21,), device=dev, generator=gen)
-        out = torch.empty(1 << 21, 128, device=dev)
-        groups = {"keys": [f"keys{b}" for b in range(nb)], "small": ["ld", "lp"]}
-        names = ["E", "A", "PE", "PA", "scratch", "keys", "small"] + [f"grads{b}" for b in range(nb)]
-        gsize = {n_: sum(sizes[m] for m in groups[n_]) + 4096 * len(groups[n_]) if n_ in groups else sizes[n_] for n_ in names}
-        # the level of the fast part: probe the whole memory in 16 GiB blocks (not for small workloads)
-        blocks, rates = [], []
-        if max(gsize.values()) >= (1 << 30):
-            try:
-                while len(blocks) < 16:
-                    blocks.append(torch.empty(16 << 30, dtype=torch.uint8, device=dev))
-            except RuntimeError:
-                pass
-            while blocks:
-                rates.append(row_probe(blocks[-1], out, idx))
-                blocks.pop()
-            torch.cuda.empty_cache()
-        fast = max(rates) if rates else 0.0
-        probe_log["survey_GBps"] = [round(r) for r in rates]
-        kept, held, tries_total = {}, [], 0
-        for n_ in names:
-            tries = 0
-            while True:
-                try:
-                    t = torch.empty(gsize[n_], dtype=torch.uint8, device=dev)
-                except RuntimeError:                 # out of memory: give the held blocks back, take what comes
-                    held.clear()
-                    torch.cuda.empty_cache()
-                    t = torch.empty(gsize[n_], dtype=torch.uint8, device=dev)
-                    kept[n_] = t
-                    break
-                if gsize[n_] < (1 << 30):
-                    kept[n_] = t
-                    break
-                r = row_probe(t, out, idx)
-                if r >= 0.97 * fast or tries >= 8:
-                    kept[n_] = t
-                    probe_log[n_] = round(r)
-                    break
-                held.append(t)
-                tries += 1
-                tries_total += 1
-        probe_log["blocks_put_aside"] = tries_total
-        del held, out, idx
-        torch.cuda.empty_cache()
-        pieces = {}
-        for n_, t in kept.items():
-            if n_ in groups:
-                o = 0
-                for m in groups[n_]:
-                    pieces[m] = t[o:o + sizes[m]]
-                    o += (sizes[m] + 4095) // 4096 * 4096
-            else:
-                pieces[n_] = t
-        return pieces
-
+    # Physical placement is the driver's; the same kernel on the same data runs at 0.75 or at 0.63 of the
+    # HBM peak depending on where the four tables lie relative to each other (rocprofv3 counters: same
+    # request counts and hit rates, but 2.6x the DRAM-credit stalls and 11 % longer read latency at the
+    # L2's memory interface in the slow case -- the loss is on the memory side).  Probe with three updates
+    # of batch 0 and, if the apply kernel is clearly off its usual rate, release the memory and take the
+    # next arrangement.
     placement, geometries = [], []
     for trial in range(max(1, args.placement_trials)):
-        specs = [args.order] if args.order else GEOMETRIES if args.layout == "auto" else [g_ for g_ in GEOMETRIES if g_ != "probed"]
+        specs = [args.order] if args.order else GEOMETRIES if args.layout == "auto" else [g_ for g_ in GEOMETRIES if g_ != "separate"]
         spec = specs[(args.first_geometry + trial) % len(specs)]
-        probed = args.layout == "probed" or (args.layout == "auto" and spec == "probed")
-        separate = probed or args.layout == "separate" or spec == "separate"
-        geometries.append("probed" if probed else "separate" if separate else spec)
-        if probed:
-            pieces = alloc_probed()
-
-            def carve(name, dtype, shape):
-                return pieces[name].view(dtype).view(shape)
-        elif separate:
+        separate = args.layout == "separate" or spec == "separate"
+        geometries.append("separate" if separate else spec)
+        if separate:
             pieces = {name: torch.empty(sizes[name], dtype=torch.uint8, device=dev) for name in sizes}
 
             def carve(name, dtype, shape):
@@ -540,7 +448,6 @@ def main():
                    "uuid": str(getattr(torch.cuda.get_device_properties(0), "uuid", "")),
                    "compute_units": torch.cuda.get_device_properties(0).multi_processor_count},
         "placement": {"arenas_tried": len(placement), "probe_apply_frac": placement, "geometry": geometries[-1],
-                      "row_probe": probe_log,
                       "parent_process_probes": json.loads(os.environ.get("ECRM_BENCH_PARENT_PROBES", "null"))},
         "path": {"algorithmic_bytes_per_step": path_bytes, "achieved_GBps": path_gbs,
                  "frac_of_hbm_peak": path_gbs / HBM_PEAK_GBS},
@@ -641,7 +548,7 @@ def main():
 
     # ---- the same update with one plain allocation per array, as a caller who does not arrange the tables
     #      would have it (the arena above is this benchmark's own arrangement)
-    if args.separate_figure and not args.graph and geometries[-1] not in ("separate", "probed"):
+    if args.separate_figure and not args.graph and geometries[-1] != "separate":
         ctx.drop_buffers()
         keep = min(nb, 2)
         hk = [keys[b].clone() for b in range(keep)]
