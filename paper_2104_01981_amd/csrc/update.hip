@@ -833,6 +833,12 @@ __device__ __forceinline__ void apply_stripes_body(const ApplyArgs &a)
     // that every wave has work.
     const uint32_t per_ticket = min((uint32_t)ECRM_APPLY_DYNAMIC, max(1u, nchunks / (4u * wave_count())));
     uint32_t ch = wave_id() * per_ticket, left = per_ticket;
+#ifndef ECRM_KEY_PREFETCH
+#define ECRM_KEY_PREFETCH 1
+#endif
+#if ECRM_KEY_PREFETCH
+    uint32_t pf_ch = 0xFFFFFFFFu, pf_key = 0, pf_idx = 0, pf_prev = 0;
+#endif
     for (;; ++ch) {
         if (left == 0) {
             // every ticket was a first ticket: nothing to fetch (and no counter traffic for small batches)
@@ -848,14 +854,36 @@ __device__ __forceinline__ void apply_stripes_body(const ApplyArgs &a)
     for (uint32_t ch = wave_id(); ch < nchunks; ch += wave_count()) {
 #endif
         const uint32_t p0 = ch * kChunk;
-        const uint32_t wkey = p0 + lane < n ? a.sk[p0 + lane] : kNoKey;
-        const uint32_t widx = p0 + lane < n ? a.si[p0 + lane] : 0u;
-        const uint32_t prevk = p0 ? uniform(a.sk[p0 - 1]) : kNoKey;
-        uint32_t left = __shfl_up(wkey, 1, kWave);
-        if (lane == 0) left = prevk;
+        uint32_t wkey, widx, prevk;
+#if ECRM_KEY_PREFETCH
+        // The group's 64 (row, index) pairs were asked for while the previous group was being worked on;
+        // only a ticket's first group has to wait for them.  (Without this every group began with a
+        // memory latency, also the many groups that lie inside a long run and have nothing to do.)
+        if (pf_ch == ch) {
+            wkey = pf_key;
+            widx = pf_idx;
+            prevk = uniform(pf_prev);
+        } else
+#endif
+        {
+            wkey = p0 + lane < n ? a.sk[p0 + lane] : kNoKey;
+            widx = p0 + lane < n ? a.si[p0 + lane] : 0u;
+            prevk = p0 ? uniform(a.sk[p0 - 1]) : kNoKey;
+        }
+#if ECRM_KEY_PREFETCH
+        if (left > 0 && ch + 1 < nchunks) {
+            const uint32_t q0 = p0 + kChunk;
+            pf_key = q0 + lane < n ? a.sk[q0 + lane] : kNoKey;
+            pf_idx = q0 + lane < n ? a.si[q0 + lane] : 0u;
+            pf_prev = a.sk[q0 - 1];
+            pf_ch = ch + 1;
+        }
+#endif
+        uint32_t leftk = __shfl_up(wkey, 1, kWave);
+        if (lane == 0) leftk = prevk;
         const bool valid = wkey != kNoKey;
-        const bool rh = !valid || left == kNoKey || left != wkey;      // lanes past n end the last run
-        const bool sh = valid && (left == kNoKey || left / k != wkey / k);
+        const bool rh = !valid || leftk == kNoKey || leftk != wkey;    // lanes past n end the last run
+        const bool sh = valid && (leftk == kNoKey || leftk / k != wkey / k);
         const unsigned long long rowheads = __ballot(rh);
         const unsigned long long stripeheads = __ballot(sh);
         const uint32_t vend = min((uint32_t)kWave, n - p0);
