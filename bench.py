@@ -24,12 +24,12 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 LONG_RUN = 1024          # ECRM_LONG_RUN of include/ecrm.h: longer runs leave the apply kernel for the split-chain path
-# HBM bytes per launch of the apply kernel on the default workload, from rocprofv3 FETCH_SIZE and
-# WRITE_SIZE scaled by a plain copy of known size (profiles/update_path_hbm_scale_hbm_traffic.txt).
-# Reported only while the code of the kernel's sources is what the counters were taken on.
-TRAFFIC_BYTES_PER_LAUNCH = 38002565724
+# HBM bytes per launch of the apply kernel, from rocprofv3 FETCH_SIZE and WRITE_SIZE scaled by a plain copy of known
+# size (profiles/update_path_<workload>_hbm_traffic.txt).  Reported only while the code of the kernel's sources is
+# what the counters were taken on.
+TRAFFIC_BYTES_PER_LAUNCH = {"hbm_scale": 38002320656, "large_uniform": 77524665682, "large_skewed": 43075737516}
 TRAFFIC_SOURCES = ["paper_2104_01981_amd/csrc/update.hip", "paper_2104_01981_amd/csrc/ecrm_internal.h"]
-TRAFFIC_SOURCES_SHA256 = "92d3c3a1ac2f43a283634fb2b53dc7adb3368e5bb921c46d720ff80a187ae990"
+TRAFFIC_SOURCES_SHA256 = "94acba8d1564b4630db4790f25326e7684903297c86c381da1f96cb1f53a05f2"
 
 
 def code_digest(paths):
@@ -50,9 +50,9 @@ def measured_traffic(workload, scale_shift, variant=""):
         digest = code_digest(TRAFFIC_SOURCES)
     except OSError:
         return None
-    if workload != "hbm_scale" or scale_shift or variant or digest != TRAFFIC_SOURCES_SHA256:
+    if workload not in TRAFFIC_BYTES_PER_LAUNCH or scale_shift or variant or digest != TRAFFIC_SOURCES_SHA256:
         return None
-    return TRAFFIC_BYTES_PER_LAUNCH
+    return TRAFFIC_BYTES_PER_LAUNCH[workload]
 
 
 def log(*a):
