@@ -103,7 +103,8 @@ int ecrm_bind(ecrm_ctx *ctx, float *E, float *A, float *PE, float *PA,
               uint64_t *load_data, uint64_t *load_parity, void *scratch, size_t scratch_bytes);
 
 /* Sum encoder with r = 1 (Sec. 3.2 "Encoder and decoder"): PE[g] = sum_j E[k*g+j], PA likewise,
- * accumulated in fp64 and rounded once.  Run once before training (Sec. 3.1). */
+ * accumulated in fp64 and rounded once.  Run once before training (Sec. 3.1).  ESTATE while a
+ * recovery (ecrm_recovery_begin) is in progress. */
 int ecrm_encode(ecrm_ctx *ctx, void *hip_stream);
 
 /* Rotating parity placement (Sec. 3.2) for n keys: stripe = key / k, member = key % k,
@@ -161,7 +162,8 @@ int ecrm_update_static(ecrm_ctx *ctx, float *E, float *A, float *PE, float *PA, 
  *                     the fly from the parity and the other members, all others are copied.  Pass
  *                     ECRM_NO_SERVER for a plain gather.  Keys >= rows raise the sticky EKEYRANGE
  *                     status and leave their output rows unwritten.
- * server >= S (other than ECRM_NO_SERVER for the read) is EINVAL. */
+ * server >= S (other than ECRM_NO_SERVER for the read) is EINVAL; ecrm_fail_server and
+ * ecrm_recover_server return ESTATE while a chunked recovery (ecrm_recovery_begin) is in progress. */
 #define ECRM_NO_SERVER 0xFFFFFFFFu
 int ecrm_fail_server(ecrm_ctx *ctx, uint32_t server, void *hip_stream);
 int ecrm_recover_server(ecrm_ctx *ctx, uint32_t server, void *hip_stream);

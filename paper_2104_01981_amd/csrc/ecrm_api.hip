@@ -74,7 +74,11 @@ static Layout make_layout(uint32_t max_batch, uint32_t D, uint32_t S, bool has_p
 {
     Layout l;
     l.max_batch = max_batch;
+    // blocks of a sort launch: large tiles, or small ones for a batch of at most kSmallSortBatch items
+    const uint32_t small_tile = kSortThreads * kSmallSortIpt;
+    const uint32_t small_blocks = max_batch >= kSmallSortBatch ? kSmallSortBlocks : (max_batch + small_tile - 1) / small_tile;
     l.max_blocks = (max_batch + kSortTile - 1) / kSortTile;
+    if (l.max_blocks < small_blocks) l.max_blocks = small_blocks;
     l.max_slots = max_batch / kLongRun + 1;
     l.max_pieces = max_batch / kPieceMin + l.max_slots + 1;
     const size_t n = max_batch;
@@ -253,6 +257,7 @@ int ecrm_encode(ecrm_ctx *c, void *stream)
 {
     if (!c) return ECRM_EINVAL;
     if (!c->bound) return ECRM_ENOTBOUND;
+    if (c->rv.active) return ECRM_ESTATE;      // rows of the lost server are not there to be summed
     launch_encode(c->geo, c->t.E, c->t.A, c->t.PE, c->t.PA, c->grid_blocks, (hipStream_t)stream);
     return check_launch();
 }
@@ -533,6 +538,7 @@ int ecrm_fail_server(ecrm_ctx *c, uint32_t server, void *stream)
     if (!c) return ECRM_EINVAL;
     if (!c->bound) return ECRM_ENOTBOUND;
     if (server >= c->geo.S) return ECRM_EINVAL;
+    if (c->rv.active) return ECRM_ESTATE;      // a second loss during a recovery is more than r = 1 tolerates
     launch_fail_server(c->geo, c->t.E, c->t.A, c->t.PE, c->t.PA, server, c->grid_blocks, (hipStream_t)stream);
     return check_launch();
 }
@@ -542,6 +548,7 @@ int ecrm_recover_server(ecrm_ctx *c, uint32_t server, void *stream)
     if (!c) return ECRM_EINVAL;
     if (!c->bound) return ECRM_ENOTBOUND;
     if (server >= c->geo.S) return ECRM_EINVAL;
+    if (c->rv.active) return ECRM_ESTATE;      // the chunked protocol is rebuilding; updates are waiting for it
     launch_recover_server(c->geo, c->t.E, c->t.A, c->t.PE, c->t.PA, server, c->grid_blocks, (hipStream_t)stream);
     return check_launch();
 }
@@ -630,9 +637,13 @@ int ecrm_profile(ecrm_ctx *c, int enable)
 {
     if (!c) return ECRM_EINVAL;
     if (enable && !c->ev_made) {
-        for (int i = 0; i < ECRM_PROFILE_MAX_CALLS; ++i)
-            for (int j = 0; j <= 2 * ECRM_PHASES; ++j)
-                if (hipEventCreate(&c->ev[i][j]) != hipSuccess) return ECRM_EHIP;
+        const int per_call = 2 * ECRM_PHASES + 1;
+        for (int e = 0; e < ECRM_PROFILE_MAX_CALLS * per_call; ++e) {
+            if (hipEventCreate(&c->ev[e / per_call][e % per_call]) != hipSuccess) {
+                while (--e >= 0) (void)hipEventDestroy(c->ev[e / per_call][e % per_call]);
+                return ECRM_EHIP;
+            }
+        }
         c->ev_made = true;
     }
     c->profiling = enable != 0;

@@ -18,6 +18,11 @@ constexpr int kSortWaves = kSortThreads / kWave;
 #endif
 constexpr int kSortIpt = ECRM_SORT_IPT;   // items per thread
 constexpr int kSortTile = kSortThreads * kSortIpt;   // 6144 items per block: 68 KB of LDS, two blocks per CU
+// Batches of at most kSmallSortBatch items are sorted in tiles of kSortThreads * kSmallSortIpt items instead: with
+// the large tile a 2^16-item batch would occupy 11 of the compute units.
+constexpr int kSmallSortIpt = 2;
+constexpr uint32_t kSmallSortBatch = 1u << 19;
+constexpr uint32_t kSmallSortBlocks = kSmallSortBatch / (kSortThreads * kSmallSortIpt);
 constexpr int kMaxRadixBits = 9;
 constexpr int kMaxBins = 1 << kMaxRadixBits;
 // Rows with more updates than this use the split-chain path (their gradients are read twice there);

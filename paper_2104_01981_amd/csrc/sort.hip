@@ -112,7 +112,7 @@ __device__ __forceinline__ uint32_t first_pass_key(uint64_t k64, uint32_t rows, 
 // ---- histogram ---------------------------------------------------------------------------------
 // FIRST: keys are the caller's u64 row ids; also range check + load accounting (count != 0).  by_stripe
 // groups by row id / k instead (for the parity half of gradient propagation).
-template <bool FIRST>
+template <bool FIRST, int IPT>
 __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
     const void *keys_in, uint32_t n, const uint32_t *n_dev, uint32_t nblocks, int shift, int bits, uint32_t *block_hist,
     Header *hdr, unsigned long long *cnt, uint32_t rows, Divider dk, Divider dS, uint32_t count, RecoveryView rv,
@@ -131,12 +131,13 @@ __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
         if (tid == 0) s_bad = 0;
     }
     __syncthreads();
-    const uint32_t tile = tile_of_block(blockIdx.x, nblocks), tile0 = tile * (uint32_t)kSortTile;
+    const uint32_t tile = tile_of_block(blockIdx.x, nblocks), tile0 = tile * (uint32_t)(kSortThreads * IPT);
     const uint32_t wave = tid / kWave, lane = lane_id();
     bool bad = false;
-#pragma unroll 4
-    for (int r = 0; r < kSortIpt; ++r) {
-        const uint32_t i = tile0 + wave * (kWave * kSortIpt) + r * kWave + lane;
+    constexpr int kUnroll = IPT < 4 ? IPT : 4;
+#pragma unroll kUnroll
+    for (int r = 0; r < IPT; ++r) {
+        const uint32_t i = tile0 + wave * (kWave * IPT) + r * kWave + lane;
         if (i < n) {
             uint32_t key;
             if (FIRST) {
@@ -190,14 +191,15 @@ __global__ __launch_bounds__(kSortThreads) void sort_scan_kernel(uint32_t *block
 #ifndef ECRM_SORT_WAVES
 #define ECRM_SORT_WAVES 4
 #endif
-template <bool FIRST>
+template <bool FIRST, int IPT>
 __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_kernel(
     const void *keys_in, const uint32_t *vals_in, uint32_t *keys_out, uint32_t *vals_out,
     const uint32_t *block_hist, const uint32_t *bin_total, uint32_t n, const uint32_t *n_dev, uint32_t nblocks, int shift,
     int bits, uint32_t rows, Divider dk, Divider dS, RecoveryView rv, uint32_t by_stripe, uint32_t packed)
 {
-    __shared__ uint32_t s_keys[kSortTile];
-    __shared__ uint32_t s_vals[kSortTile];
+    constexpr uint32_t kTile = kSortThreads * IPT;
+    __shared__ uint32_t s_keys[kTile];
+    __shared__ uint32_t s_vals[kTile];
     __shared__ uint32_t s_wcnt[kSortWaves][kMaxBins];   // per-wave digit counts, then wave offsets
     __shared__ uint32_t s_binstart[kMaxBins];           // start of the digit inside the sorted tile
     __shared__ uint32_t s_gbase[kMaxBins];              // global position of sorted-tile slot 0 of the digit
@@ -209,11 +211,11 @@ __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_ke
     for (uint32_t i = tid; i < kSortWaves * kMaxBins; i += kSortThreads) (&s_wcnt[0][0])[i] = 0;
     __syncthreads();
 
-    const uint32_t tile = tile_of_block(blockIdx.x, nblocks), tile0 = tile * (uint32_t)kSortTile;
-    uint32_t key[kSortIpt], val[kSortIpt], rank[kSortIpt];
+    const uint32_t tile = tile_of_block(blockIdx.x, nblocks), tile0 = tile * kTile;
+    uint32_t key[IPT], val[IPT], rank[IPT];
 #pragma unroll
-    for (int r = 0; r < kSortIpt; ++r) {
-        const uint32_t i = tile0 + wave * (kWave * kSortIpt) + r * kWave + lane;
+    for (int r = 0; r < IPT; ++r) {
+        const uint32_t i = tile0 + wave * (kWave * IPT) + r * kWave + lane;
         key[r] = 0;
         val[r] = 0;
         if (i < n) {
@@ -232,8 +234,8 @@ __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_ke
     // rank inside the wave: items are ordered (r, lane); equal digits are matched with ballots
     const unsigned long long lt = (1ull << lane) - 1ull;
 #pragma unroll
-    for (int r = 0; r < kSortIpt; ++r) {
-        const uint32_t i = tile0 + wave * (kWave * kSortIpt) + r * kWave + lane;
+    for (int r = 0; r < IPT; ++r) {
+        const uint32_t i = tile0 + wave * (kWave * IPT) + r * kWave + lane;
         const bool valid = i < n;
         const uint32_t digit = (key[r] >> shift) & mask;
         unsigned long long peers = __ballot(valid);
@@ -274,8 +276,8 @@ __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_ke
     __syncthreads();
 
 #pragma unroll
-    for (int r = 0; r < kSortIpt; ++r) {
-        const uint32_t i = tile0 + wave * (kWave * kSortIpt) + r * kWave + lane;
+    for (int r = 0; r < IPT; ++r) {
+        const uint32_t i = tile0 + wave * (kWave * IPT) + r * kWave + lane;
         if (i < n) {
             const uint32_t digit = (key[r] >> shift) & mask;
             const uint32_t pos = s_binstart[digit] + s_wcnt[wave][digit] + rank[r];
@@ -285,7 +287,7 @@ __global__ __launch_bounds__(kSortThreads, ECRM_SORT_WAVES) void sort_scatter_ke
     }
     __syncthreads();
 
-    const uint32_t count = tile0 < n ? min((uint32_t)kSortTile, n - tile0) : 0u;
+    const uint32_t count = tile0 < n ? min(kTile, n - tile0) : 0u;
     for (uint32_t i = tid; i < count; i += kSortThreads) {
         const uint32_t kk = s_keys[i];
         const uint32_t gpos = s_gbase[(kk >> shift) & mask] + i;
@@ -311,13 +313,39 @@ void launch_clear_status(const Scratch &s, hipStream_t st)
     hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, st, s.hdr);
 }
 
+// One digit of the sort with tiles of kSortThreads * IPT items.
+template <int IPT>
+static void launch_sort_pass(const Scratch &s, const Geometry &g, const RecoveryView &rv, bool first, const void *keys_in,
+                             const uint32_t *vals_in, uint32_t *keys_out, uint32_t *vals_out, uint32_t n,
+                             const uint32_t *n_dev, int shift, int bits, uint32_t count, uint32_t by_stripe,
+                             uint32_t packed, hipStream_t st)
+{
+    const uint32_t tile = kSortThreads * IPT, nblocks = (n + tile - 1) / tile, bins = 1u << bits;
+    if (first)
+        hipLaunchKernelGGL((sort_hist_kernel<true, IPT>), dim3(nblocks), dim3(kSortThreads), 0, st, keys_in, n, n_dev,
+                           nblocks, shift, bits, s.block_hist, s.hdr, s.cnt, g.rows, g.dk, g.dS, count, rv, by_stripe, packed);
+    else
+        hipLaunchKernelGGL((sort_hist_kernel<false, IPT>), dim3(nblocks), dim3(kSortThreads), 0, st, keys_in, n, n_dev,
+                           nblocks, shift, bits, s.block_hist, s.hdr, s.cnt, g.rows, g.dk, g.dS, 0u, rv, 0u, 0u);
+    hipLaunchKernelGGL(sort_scan_kernel, dim3(bins), dim3(kSortThreads), 0, st, s.block_hist, s.bin_total, nblocks);
+    if (first)
+        hipLaunchKernelGGL((sort_scatter_kernel<true, IPT>), dim3(nblocks), dim3(kSortThreads), 0, st, keys_in, vals_in,
+                           keys_out, vals_out, s.block_hist, s.bin_total, n, n_dev, nblocks, shift, bits, g.rows, g.dk,
+                           g.dS, rv, by_stripe, packed);
+    else
+        hipLaunchKernelGGL((sort_scatter_kernel<false, IPT>), dim3(nblocks), dim3(kSortThreads), 0, st, keys_in, vals_in,
+                           keys_out, vals_out, s.block_hist, s.bin_total, n, n_dev, nblocks, shift, bits, g.rows, g.dk,
+                           g.dS, rv, 0u, 0u);
+}
+
 void launch_sort(const Scratch &s, const Geometry &g, const RecoveryView &rv, const uint64_t *keys, uint32_t n,
                  const uint32_t *n_dev, BatchSource src, int key_bits, bool by_stripe, bool count_servers,
                  uint32_t **sorted_keys, uint32_t **sorted_vals, hipStream_t st)
 {
     const uint32_t count = (count_servers && !(g.mode & 2u)) ? 1u : 0u, bs = by_stripe ? 1u : 0u;
     const uint32_t packed = src == kWaitingUpdates ? 1u : 0u;
-    const uint32_t nblocks = (n + kSortTile - 1) / kSortTile;
+    // a small batch is cut into small tiles, so that it still spreads over the compute units
+    const bool small = n <= kSmallSortBatch;
     int passes = (key_bits + kMaxRadixBits - 1) / kMaxRadixBits;
     if (passes < 1) passes = 1;
     int shift = 0, cur = 0;
@@ -326,28 +354,16 @@ void launch_sort(const Scratch &s, const Geometry &g, const RecoveryView &rv, co
         const int left = key_bits - shift;
         int bits = (left + (passes - p) - 1) / (passes - p);
         if (bits < 1) bits = 1;
-        const uint32_t bins = 1u << bits;
-        if (p == 0) {
-            hipLaunchKernelGGL(sort_hist_kernel<true>, dim3(nblocks), dim3(kSortThreads), 0, st,
-                               (const void *)keys, n, n_dev, nblocks, shift, bits, s.block_hist, s.hdr, s.cnt,
-                               g.rows, g.dk, g.dS, count, rv, bs, packed);
-            hipLaunchKernelGGL(sort_scan_kernel, dim3(bins), dim3(kSortThreads), 0, st, s.block_hist,
-                               s.bin_total, nblocks);
-            hipLaunchKernelGGL(sort_scatter_kernel<true>, dim3(nblocks), dim3(kSortThreads), 0, st,
-                               (const void *)keys, (const uint32_t *)nullptr, s.keys[0], s.vals[0],
-                               s.block_hist, s.bin_total, n, n_dev, nblocks, shift, bits, g.rows, g.dk, g.dS, rv, bs, packed);
-            cur = 0;
-        } else {
-            hipLaunchKernelGGL(sort_hist_kernel<false>, dim3(nblocks), dim3(kSortThreads), 0, st,
-                               (const void *)s.keys[cur], n, n_dev, nblocks, shift, bits, s.block_hist, s.hdr,
-                               s.cnt, g.rows, g.dk, g.dS, 0u, rv, 0u, 0u);
-            hipLaunchKernelGGL(sort_scan_kernel, dim3(bins), dim3(kSortThreads), 0, st, s.block_hist,
-                               s.bin_total, nblocks);
-            hipLaunchKernelGGL(sort_scatter_kernel<false>, dim3(nblocks), dim3(kSortThreads), 0, st,
-                               (const void *)s.keys[cur], s.vals[cur], s.keys[cur ^ 1], s.vals[cur ^ 1],
-                               s.block_hist, s.bin_total, n, n_dev, nblocks, shift, bits, g.rows, g.dk, g.dS, rv, 0u, 0u);
-            cur ^= 1;
-        }
+        const void *kin = p == 0 ? (const void *)keys : (const void *)s.keys[cur];
+        const uint32_t *vin = p == 0 ? nullptr : s.vals[cur];
+        const int out = p == 0 ? 0 : cur ^ 1;
+        if (small)
+            launch_sort_pass<kSmallSortIpt>(s, g, rv, p == 0, kin, vin, s.keys[out], s.vals[out], n, n_dev, shift, bits,
+                                            count, bs, packed, st);
+        else
+            launch_sort_pass<kSortIpt>(s, g, rv, p == 0, kin, vin, s.keys[out], s.vals[out], n, n_dev, shift, bits, count,
+                                       bs, packed, st);
+        cur = out;
         shift += bits;
     }
     *sorted_keys = s.keys[cur];

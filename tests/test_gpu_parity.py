@@ -72,6 +72,9 @@ def test_medium_workload():
     (1000, 128, 1, 2, 5000),            # k = 1: the parity is a mirror of the entry
     (4 * 700, 128, 4, 1024, 9000),      # the largest number of servers
     (2 * 333, 8, 2, 3, 40000),          # very short rows, long runs (~60 updates per entry)
+    (4 * 300, 16, 4, 5, 1025),          # one item past a small sort tile
+    (4 * 40000, 8, 4, 5, 1 << 19),      # the largest batch that is sorted in small tiles
+    (4 * 40000, 8, 4, 5, (1 << 19) + 1),  # the smallest one that is sorted in large tiles
 ])
 def test_shapes(R, D, k, S, n):
     c = Case(R, D, k, S, max_batch=n, seed=17)

@@ -96,6 +96,10 @@ def test_recovery_buffer_overflow_and_state_errors():
     c.ctx.recovery_begin(server, 2, buf_keys, buf_grads, cap)
     assert c.ctx.recovery_begin(server, 2, buf_keys, buf_grads, cap, check=False) == -8
     assert c.ctx.recovery_decode(check=False) == -8                 # nothing locked
+    lib, raw = c.ctx._lib, c.ctx._ctx
+    assert lib.ecrm_encode(raw, None) == -8                         # no second loss, full rebuild or re-encoding
+    assert lib.ecrm_fail_server(raw, 1, None) == -8                 # while the chunked protocol runs
+    assert lib.ecrm_recover_server(raw, server, None) == -8
     assert c.ctx.recovery_unlock(check=False) == -8
     c.ctx.recovery_lock()
     assert c.ctx.recovery_lock(check=False) == -8
