@@ -27,9 +27,9 @@ LONG_RUN = 1024          # ECRM_LONG_RUN of include/ecrm.h: longer runs leave th
 # HBM bytes per launch of the apply kernel, from rocprofv3 FETCH_SIZE and WRITE_SIZE scaled by a plain copy of known
 # size (profiles/update_path_<workload>_hbm_traffic.txt).  Reported only while the code of the kernel's sources is
 # what the counters were taken on.
-TRAFFIC_BYTES_PER_LAUNCH = {"hbm_scale": 38002320656, "large_uniform": 77524665682, "large_skewed": 43075737516}
+TRAFFIC_BYTES_PER_LAUNCH = {"hbm_scale": 38002335262, "large_uniform": 77525425581, "large_skewed": 43075735199}
 TRAFFIC_SOURCES = ["paper_2104_01981_amd/csrc/update.hip", "paper_2104_01981_amd/csrc/ecrm_internal.h"]
-TRAFFIC_SOURCES_SHA256 = "94acba8d1564b4630db4790f25326e7684903297c86c381da1f96cb1f53a05f2"
+TRAFFIC_SOURCES_SHA256 = "a570661d5032d73d0949d6216f394cdfff7bb4e5ea5c170e1fa7ae9a4852dad6"
 
 
 def code_digest(paths):
