@@ -27,9 +27,9 @@ LONG_RUN = 1024          # ECRM_LONG_RUN of include/ecrm.h: longer runs leave th
 # HBM bytes per launch of the apply kernel, from rocprofv3 FETCH_SIZE and WRITE_SIZE scaled by a plain copy of known
 # size (profiles/update_path_<workload>_hbm_traffic.txt).  Reported only while the code of the kernel's sources is
 # what the counters were taken on.
-TRAFFIC_BYTES_PER_LAUNCH = {"hbm_scale": 38002335262, "large_uniform": 77525425581, "large_skewed": 43075735199}
+TRAFFIC_BYTES_PER_LAUNCH = {"hbm_scale": 38002218916, "large_uniform": 77525602221, "large_skewed": 43075325362}
 TRAFFIC_SOURCES = ["paper_2104_01981_amd/csrc/update.hip", "paper_2104_01981_amd/csrc/ecrm_internal.h"]
-TRAFFIC_SOURCES_SHA256 = "a570661d5032d73d0949d6216f394cdfff7bb4e5ea5c170e1fa7ae9a4852dad6"
+TRAFFIC_SOURCES_SHA256 = "39e7ef2c97bbaabbc6036ff3c93bde0b97b3c7be1da1b2dc97674eebe0d38dd8"
 
 
 def code_digest(paths):

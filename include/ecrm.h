@@ -236,7 +236,15 @@ int ecrm_clear_status(ecrm_ctx *ctx, void *hip_stream);
  * ecrm_batch_stats waits for the stream and reports what the LAST ecrm_update found:
  *   out[0] = entries updated through the split-chain path (more than ECRM_LONG_RUN updates)
  *   out[1] = chain pieces those were cut into,  out[2] = items in those entries,
- *   out[3] = 1 if the batch was rejected for a bad key.
+ *   out[3] = 1 if the batch was rejected for a bad key,
+ *   out[4] = how many of the out[0] entries were walked by one workgroup each, with one read of their
+ *            gradients (see ecrm_tune), instead of being cut into pieces.
+ * ecrm_tune sets a tuning knob of the context (tests and measurements; the library is measured with the
+ * defaults).  ECRM_TUNE_MID_MIN_ROWS: on the Adagrad rule an entry with more than ECRM_LONG_RUN and at most
+ * ECRM_MID_RUN updates in a call is walked by one workgroup -- one read of its gradients instead of two --
+ * but only in calls with at least this many such long entries, since one workgroup is slow and pays only
+ * when all of them are busy.  Default (value 0): four per workgroup the device holds at once.  EINVAL for
+ * an unknown knob or a value above 2^32-1.
  * ecrm_host_placement runs on the HOST only (no GPU needed): it evaluates, with the very 32-bit
  * arithmetic the kernels use, where `key` lies -- out[0] = stripe, out[1] = member, out[2] = data
  * server, out[3] = parity server (Sec. 3.2) -- and, for a recovery of `failed_server` in `chunks`
@@ -245,7 +253,9 @@ int ecrm_clear_status(ecrm_ctx *ctx, void *hip_stream);
  * holds (member index, k for the parity, 0xFFFFFFFF for none).  EINVAL for key >= rows, a bad server
  * or chunk count. */
 enum { ECRM_PHASE_GROUP = 0, ECRM_PHASE_CHAINS = 1, ECRM_PHASE_APPLY = 2, ECRM_PHASES = 3 };
-enum { ECRM_PROFILE_MAX_CALLS = 256, ECRM_LONG_RUN = 1024 };
+enum { ECRM_PROFILE_MAX_CALLS = 256, ECRM_LONG_RUN = 1024, ECRM_MID_RUN = 32768 };
+enum { ECRM_TUNE_MID_MIN_ROWS = 1 };
+int ecrm_tune(ecrm_ctx *ctx, int what, uint64_t value);
 int ecrm_profile(ecrm_ctx *ctx, int enable);
 int ecrm_profile_read(ecrm_ctx *ctx, double *ms, uint64_t *calls);
 int ecrm_batch_stats(ecrm_ctx *ctx, void *hip_stream, uint64_t *out);

@@ -19,7 +19,7 @@ _lib = None
 
 SYMBOLS = ["ecrm_create", "ecrm_destroy", "ecrm_data_bytes", "ecrm_parity_bytes", "ecrm_scratch_bytes",
            "ecrm_bind", "ecrm_encode", "ecrm_route", "ecrm_update", "ecrm_update_static", "ecrm_status", "ecrm_clear_status",
-           "ecrm_profile", "ecrm_profile_read", "ecrm_batch_stats", "ecrm_host_placement", "ecrm_strerror",
+           "ecrm_tune", "ecrm_profile", "ecrm_profile_read", "ecrm_batch_stats", "ecrm_host_placement", "ecrm_strerror",
            "ecrm_fail_server", "ecrm_recover_server", "ecrm_degraded_read",
            "ecrm_recovery_begin", "ecrm_recovery_lock", "ecrm_recovery_decode", "ecrm_recovery_unlock",
            "ecrm_recovery_state", "ecrm_recovery_read"]
@@ -72,6 +72,7 @@ def load_library():
                                             C.POINTER(C.c_uint32), C.POINTER(C.c_uint64)]
         lib.ecrm_status.argtypes = [vp, vp]
         lib.ecrm_clear_status.argtypes = [vp, vp]
+        lib.ecrm_tune.argtypes = [vp, C.c_int, C.c_uint64]
         lib.ecrm_profile.argtypes = [vp, C.c_int]
         lib.ecrm_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
         lib.ecrm_batch_stats.argtypes = [vp, vp, C.POINTER(C.c_uint64)]
@@ -271,8 +272,14 @@ class Ecrm:
         return [int(v) for v in out]
 
     def batch_stats(self, stream=None):
-        out = (C.c_uint64 * 4)()
+        out = (C.c_uint64 * 5)()
         rc = self._lib.ecrm_batch_stats(self._ctx, _stream(stream), out)
         if rc != ECRM_OK:
             raise EcrmError(rc, "ecrm_batch_stats")
-        return dict(long_rows=int(out[0]), pieces=int(out[1]), long_items=int(out[2]), rejected=int(out[3]))
+        return dict(long_rows=int(out[0]), pieces=int(out[1]), long_items=int(out[2]), rejected=int(out[3]),
+                    one_workgroup_rows=int(out[4]))
+
+    def tune(self, what, value):
+        rc = self._lib.ecrm_tune(self._ctx, C.c_int(what), C.c_uint64(value))
+        if rc != ECRM_OK:
+            raise EcrmError(rc, "ecrm_tune")

@@ -38,6 +38,7 @@ struct ecrm_ctx {
     int grid_blocks;          // 8 blocks of 256 threads per CU, for the streaming kernels
     int cus;
     LaunchGrids lg;           // resident grids of the grid-stride kernels (filled by ecrm_bind)
+    uint32_t tune_mid_min_rows;   // ecrm_tune: replaces lg.mid_min_rows when not 0
     // recovery in progress (host-side state machine; the device sees it as a RecoveryView per call)
     RecoveryView rv;
     uint32_t rec_chunks;
@@ -90,7 +91,7 @@ static Layout make_layout(uint32_t max_batch, uint32_t D, uint32_t S, bool has_p
     l.off_hist = take((size_t)kMaxBins * l.max_blocks * 4);
     l.off_bintotal = take(kMaxBins * 4);
     l.off_long_slot = take(n * 4);
-    l.off_long_meta = take((size_t)5 * l.max_slots * 4);
+    l.off_long_meta = take((size_t)(5 + kMidClasses) * l.max_slots * 4);
     l.off_piece_slot = take((size_t)l.max_pieces * 4);
     l.off_partial = take((size_t)l.max_pieces * D * sizeof(double));
     l.off_partial2 = take(has_partial2 ? (size_t)l.max_pieces * D * sizeof(double) : 0);
@@ -118,6 +119,7 @@ static Scratch carve(const Layout &l, void *base, bool has_partial2)
     s.long_piece = meta + (size_t)2 * l.max_slots;
     s.long_count = meta + (size_t)3 * l.max_slots;
     s.long_base = meta + (size_t)4 * l.max_slots;
+    s.mid_list = meta + (size_t)5 * l.max_slots;
     s.piece_slot = (uint32_t *)(b + l.off_piece_slot);
     s.partial = (double *)(b + l.off_partial);
     s.partial2 = has_partial2 ? (double *)(b + l.off_partial2) : nullptr;
@@ -292,15 +294,17 @@ static int run_update(ecrm_ctx *c, const Tables &t, const Scratch &s, const Layo
     if (rv.active)
         while (key_bits < 32 && (1ull << key_bits) <= c->cfg.rows) ++key_bits;
     const uint32_t prop = c->cfg.propagation;
+    LaunchGrids lg = c->lg;
+    if (c->tune_mid_min_rows) lg.mid_min_rows = c->tune_mid_min_rows;
     uint32_t *sk = nullptr, *si = nullptr;
     launch_sort(s, c->geo, rv, keys, n32, n_dev, src, key_bits, false, true, &sk, &si, st);
     if (rv.active || src == kWaitingUpdates)
         launch_hold_back(s, c->geo, rv, keys, grads, n32, src, c->hb, c->buf_cur, st);
     if (ev) (void)hipEventRecord(ev[1], st);
-    launch_chains(s, c->geo, c->lg, t.A, grads, sk, si, n32, l.max_slots, l.max_pieces, c->cus, st);
+    launch_chains(s, c->geo, lg, t.A, grads, sk, si, n32, l.max_slots, l.max_pieces, c->cus, st);
     if (ev) (void)hipEventRecord(ev[2], st);
     const bool diff = prop == ECRM_PROP_DIFFERENCE;
-    launch_apply(s, c->geo, c->lg, t.E, t.A, diff ? t.PE : nullptr, diff ? t.PA : nullptr, t.load_data,
+    launch_apply(s, c->geo, lg, t.E, t.A, diff ? t.PE : nullptr, diff ? t.PA : nullptr, t.load_data,
                  prop == ECRM_PROP_NONE ? nullptr : t.load_parity, grads, sk, si, n32, c->cus, st);
     if (prop == ECRM_PROP_GRADIENT) {
         // The strawman of Sec. 3.3.1: the parity server receives the gradient itself and applies the
@@ -315,9 +319,9 @@ static int run_update(ecrm_ctx *c, const Tables &t, const Scratch &s, const Layo
         launch_reset(s, c->geo.S, n32, false, kCallerBatch, st);
         launch_sort(s, c->geo, rv, keys, n32, nullptr, kCallerBatch, bits, true, false, &sk, &si, st);
         if (ev) (void)hipEventRecord(ev[4], st);
-        launch_chains(s, gp, c->lg, t.PA, grads, sk, si, n32, l.max_slots, l.max_pieces, c->cus, st);
+        launch_chains(s, gp, lg, t.PA, grads, sk, si, n32, l.max_slots, l.max_pieces, c->cus, st);
         if (ev) (void)hipEventRecord(ev[5], st);
-        launch_apply(s, gp, c->lg, t.PE, t.PA, nullptr, nullptr, nullptr, nullptr, grads, sk, si, n32, c->cus, st);
+        launch_apply(s, gp, lg, t.PE, t.PA, nullptr, nullptr, nullptr, nullptr, grads, sk, si, n32, c->cus, st);
         if (ev) (void)hipEventRecord(ev[6], st);
     } else if (ev) {
         (void)hipEventRecord(ev[3], st);
@@ -601,6 +605,8 @@ int ecrm_batch_stats(ecrm_ctx *c, void *stream, uint64_t *out)
     out[1] = h.n_pieces;
     out[2] = h.n_long_items;
     out[3] = h.batch_bad;
+    out[4] = 0;
+    for (uint32_t cl = 0; cl < kMidClasses; ++cl) out[4] += h.n_mid[cl];
     return ECRM_OK;
 }
 
@@ -630,6 +636,14 @@ int ecrm_host_placement(const ecrm_ctx *c, uint64_t key, uint32_t failed_server,
     if (!divider_ok(rv.dspc)) return ECRM_EINVAL;
     out[4] = held_back(rv, x, c->geo.dk, c->geo.dS) ? 1u : 0u;
     out[5] = (uint32_t)unit_on_server(g, k, c->geo.S, failed_server);
+    return ECRM_OK;
+}
+
+int ecrm_tune(ecrm_ctx *c, int what, uint64_t value)
+{
+    if (!c) return ECRM_EINVAL;
+    if (what != ECRM_TUNE_MID_MIN_ROWS || value > 0xFFFFFFFFull) return ECRM_EINVAL;
+    c->tune_mid_min_rows = (uint32_t)value;
     return ECRM_OK;
 }
 

@@ -31,6 +31,17 @@ constexpr int kMaxBins = 1 << kMaxRadixBits;
 constexpr uint32_t kLongRun = ECRM_LONG_RUN;
 constexpr uint32_t kPieceMin = 128;  // smallest chain piece
 constexpr uint32_t kPieceMaxCount = 1024;     // a chain is cut into at most this many pieces
+// Adagrad runs of more than kLongRun and at most kMidMax updates are walked by ONE workgroup that keeps the
+// gradients in registers between the sum of squares and the steps (one read); only longer runs, which need
+// many workgroups, go through the pieces and read their gradients twice.  0 = no such tier.  One workgroup
+// takes ~0.5 ms over 32768 updates, so this pays only when there are enough such runs to keep every
+// workgroup busy meanwhile: with fewer than kMidMinRowsPerBlock long rows per resident workgroup all runs
+// go through the pieces (measured: 3801 long rows, 49 % of 2^26 updates -- chains 6.8 -> 5.2 ms; 420 long
+// rows in 2^24 updates -- 0.66 -> 1.1 ms if the tier were used there).
+constexpr uint32_t kMidMax = ECRM_MID_RUN;
+constexpr uint32_t kMidMinRowsPerBlock = 4;
+constexpr int kMidWaves = 8;         // waves of the workgroup that walks such a run
+constexpr uint32_t kMidClasses = 7;  // the runs are listed by length (x2 per class) and taken longest first
 #ifndef ECRM_CHUNK
 #define ECRM_CHUNK 16
 #endif
@@ -53,7 +64,9 @@ struct Header {
                            // replayed -- what buf_count was when the replay started (set by reset)
     uint32_t free_count;   // slots of the recovery buffer's row pool that were released and can be reused
     uint32_t bump;         // slots of the row pool that have ever been handed out
-    uint32_t pad[51];
+    uint32_t n_mid[kMidClasses];   // long rows of this batch that one workgroup walks, by length class
+    uint32_t mid_ticket;   // next of them to be handed out (cleared by reset)
+    uint32_t pad[43];
 };
 static_assert(sizeof(Header) == 256, "header is one 256-byte block");
 
@@ -66,6 +79,7 @@ struct Scratch {           // device pointers carved out of the caller's scratch
     uint32_t *bin_total;           // [bins]
     uint32_t *long_slot;           // [n] slot id, valid at heads of long rows only
     uint32_t *long_head, *long_len, *long_piece, *long_count, *long_base;   // [max_slots]
+    uint32_t *mid_list;            // [kMidClasses][max_slots] slots of the rows one workgroup walks
     uint32_t *piece_slot;          // [max_pieces]
     double *partial;               // [max_pieces][D]
     double *partial2;              // [max_pieces][D], momentum SGD only (else null)
@@ -154,6 +168,8 @@ struct Geometry {
 // once.  Filled once per context when it learns its device (never inside a stream capture).
 struct LaunchGrids {
     int p1, p3;            // chain pieces: summaries, steps
+    int mid;               // runs walked by one workgroup
+    uint32_t mid_min_rows; // ... which is done only in batches with at least this many long rows
     int apply, rows;       // apply with / without the parity rows
 };
 bool query_launch_grids(const Geometry &g, int cus, LaunchGrids *out);   // false: an occupancy query failed

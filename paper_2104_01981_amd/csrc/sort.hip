@@ -62,6 +62,8 @@ __global__ void reset_kernel(Header *h, unsigned long long *cnt, uint32_t S, uin
         h->n_valid = n;
         h->n_held = 0;
         h->apply_ticket = 0;
+        for (uint32_t c = 0; c < kMidClasses; ++c) h->n_mid[c] = 0;
+        h->mid_ticket = 0;
     }
     for (uint32_t i = t; i < 2 * S; i += blockDim.x) cnt[i] = 0;
 }

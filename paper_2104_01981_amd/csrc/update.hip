@@ -196,15 +196,19 @@ __global__ __launch_bounds__(256) void long_find_kernel(const uint32_t *sk, uint
 }
 
 // Length of each long run (binary search for its end) and its cut into pieces.  One wave per run.
+// A run of at most mid_max updates gets no pieces: its slot goes on the list of its length class
+// (mid_chain_kernel) -- provided the batch has at least mid_min_rows long rows.
 __global__ __launch_bounds__(256) void long_plan_kernel(const uint32_t *sk, uint32_t n, Header *hdr,
                                                         const uint32_t *long_head, uint32_t *long_len,
                                                         uint32_t *long_piece, uint32_t *long_count,
                                                         uint32_t *long_base, uint32_t *piece_slot,
+                                                        uint32_t *mid_list, uint32_t mid_max, uint32_t mid_min_rows,
                                                         uint32_t max_slots, uint32_t max_pieces)
 {
     if (hdr->batch_bad) return;
     n = min(n, hdr->n_valid);
     const uint32_t nl = min(hdr->n_long, max_slots);
+    if (nl < mid_min_rows) mid_max = 0;
     const uint32_t lane = lane_id();
     for (uint32_t slot = wave_id(); slot < nl; slot += wave_count()) {
         const uint32_t p = uniform(long_head[slot]);
@@ -215,6 +219,20 @@ __global__ __launch_bounds__(256) void long_plan_kernel(const uint32_t *sk, uint
             if (uniform(sk[mid]) == x) lo = mid; else hi = mid;
         }
         const uint32_t L = hi - p;
+        if (L <= mid_max) {
+            if (lane == 0) {
+                uint32_t c = 0;
+                while (c + 1 < kMidClasses && ((L - 1) / kLongRun) >> (c + 1)) ++c;
+                const uint32_t at = atomicAdd(&hdr->n_mid[c], 1u);
+                if (at < max_slots) mid_list[(size_t)c * max_slots + at] = slot;   // always true: at most n_long such rows
+                atomicAdd(&hdr->n_long_items, (unsigned long long)L);
+                long_len[slot] = L;
+                long_piece[slot] = 0;
+                long_count[slot] = 0;
+                long_base[slot] = 0;
+            }
+            continue;
+        }
         uint32_t C = (L + kPieceMaxCount - 1) / kPieceMaxCount;
         if (C < kPieceMin) C = kPieceMin;
         const uint32_t P = (L + C - 1) / C;
@@ -337,6 +355,7 @@ __global__ __launch_bounds__(kRowWaves * kWave) void long_scan_kernel(
     for (uint32_t slot = blockIdx.x; slot < nl; slot += gridDim.x) {
         const uint32_t x = uniform(sk[long_head[slot]]);
         const uint32_t P = uniform(long_count[slot]), base = uniform(long_base[slot]);
+        if (P == 0) continue;                                        // walked by one workgroup: no pieces to scan
         const uint32_t C = uniform(long_piece[slot]), L = uniform(long_len[slot]);
         const uint32_t Q = (P + kRowWaves - 1) / kRowWaves;          // pieces per wave
         const uint32_t j_lo = min(w * Q, P), j_hi = min(j_lo + Q, P);
@@ -474,6 +493,7 @@ __global__ __launch_bounds__(kRowWaves * kWave) void long_reduce_kernel(Header *
     constexpr uint32_t U = 8;
     for (uint32_t slot = blockIdx.x; slot < nl; slot += gridDim.x) {
         const uint32_t P = uniform(long_count[slot]), base = uniform(long_base[slot]);
+        if (P == 0) continue;                                        // its totals are there already
         const uint32_t Q = (P + kRowWaves - 1) / kRowWaves;
         const uint32_t j_lo = min(w * Q, P), j_hi = min(j_lo + Q, P);
         for (uint32_t cb = 0; cb < geo.ncb; ++cb) {
@@ -519,6 +539,140 @@ __global__ __launch_bounds__(kRowWaves * kWave) void long_reduce_kernel(Header *
                     std2(res, i, tot);
                 }
             }
+        }
+    }
+}
+
+// A run of moderate length on the Adagrad rule, walked by one workgroup with one read of its gradients.
+// Per round every wave takes T consecutive updates of the run and keeps their gradient rows in registers:
+// it sums their squares, the waves exchange these sums through LDS -- so that each knows the accumulator
+// its updates start from -- and it then takes its steps from the registers.  The accumulator is carried
+// from round to round; the waves' step sums are added up once, at the end of the run.  Runs are taken
+// longest first (the lists are by length class), so that the longest one does not end the kernel alone.
+// long_res[slot] receives what the pieces' kernels would have left there: the sum of the steps and the
+// accumulator after the run.
+template <int NC>
+__global__ __launch_bounds__(kMidWaves * kWave, 4) void mid_chain_kernel(
+    const uint32_t *sk, const uint32_t *si, const float *grads, const float *A, Header *hdr, const uint32_t *long_head,
+    const uint32_t *long_len, const uint32_t *mid_list, double *long_res, uint32_t max_slots, Geometry geo)
+{
+    constexpr int T = 32 / NC;                               // gradient rows a wave holds
+    constexpr uint32_t R = kMidWaves * T;                    // updates per round
+    __shared__ double s_part[2][kMidWaves][NC][2][kWave];
+    __shared__ uint32_t s_ticket;
+    if (hdr->batch_bad) return;
+    uint32_t in_class[kMidClasses], total = 0;
+#pragma unroll
+    for (uint32_t c = 0; c < kMidClasses; ++c) {
+        in_class[c] = min(hdr->n_mid[c], max_slots);
+        total += in_class[c];
+    }
+    const uint32_t D = geo.D, lane = lane_id(), w = uniform(threadIdx.x / kWave);
+    const RuleParams rp = rule_params(geo);
+    for (;;) {
+        if (threadIdx.x == 0) s_ticket = atomicAdd(&hdr->mid_ticket, 1u);
+        __syncthreads();
+        uint32_t t = uniform(s_ticket);
+        __syncthreads();                                     // everyone has read the ticket before the next one is written
+        if (t >= total) break;
+        uint32_t c = kMidClasses - 1;
+        while (t >= in_class[c]) {                           // ends: t < total
+            t -= in_class[c];
+            --c;
+        }
+        const uint32_t slot = uniform(mid_list[(size_t)c * max_slots + t]);
+        const uint32_t head = uniform(long_head[slot]), L = uniform(long_len[slot]), x = uniform(sk[head]);
+        for (uint32_t cb = 0; cb < geo.ncb; ++cb) {
+            const uint32_t col0 = cb * NC * 128u;
+            const rsrc_t arow = row_f32(A, x, D, col0);
+            D2 G[NC], acc[NC];
+#pragma unroll
+            for (int i = 0; i < NC; ++i) {
+                G[i] = widen2(ld2(arow, i));
+                acc[i] = D2{0, 0};
+            }
+            uint32_t buf = 0;
+            for (uint32_t r0 = 0; r0 < L; r0 += R, buf ^= 1u) {
+                const uint32_t off = r0 + w * T;             // this wave's first update, counted from the head
+                const uint32_t cnt = off < L ? min((uint32_t)T, L - off) : 0u;
+                // positions past the end of the run re-read its last update; their values are not used
+                const uint32_t my_idx = si[head + min(off + lane, L - 1u)];
+                float2 g[T][NC];
+#pragma unroll
+                for (int u = 0; u < T; ++u) {
+                    const rsrc_t r = row_f32(grads, from_lane(my_idx, u), D, col0);
+#pragma unroll
+                    for (int i = 0; i < NC; ++i) g[u][i] = ldg2(r, i);
+                }
+                D2 s[NC];
+#pragma unroll
+                for (int i = 0; i < NC; ++i) s[i] = D2{0, 0};
+#pragma unroll
+                for (int u = 0; u < T; ++u) {
+                    if ((uint32_t)u < cnt) {
+#pragma unroll
+                        for (int i = 0; i < NC; ++i) summary2<kAdagradSeq>(s[i], g[u][i], rp);
+                    }
+                }
+                // the rows stay in registers as the floats they are (otherwise the compiler keeps the
+                // widened copies it made for the squares alive until the steps: three times the registers)
+#pragma unroll
+                for (int u = 0; u < T; ++u) {
+#pragma unroll
+                    for (int i = 0; i < NC; ++i) asm volatile("" : "+v"(g[u][i].x), "+v"(g[u][i].y));
+                }
+#pragma unroll
+                for (int i = 0; i < NC; ++i) {
+                    s_part[buf][w][i][0][lane] = s[i].x;
+                    s_part[buf][w][i][1][lane] = s[i].y;
+                }
+                // One barrier per round is enough: the next round writes the other half of s_part, and a wave
+                // that writes this half again (two rounds on) has passed the next round's barrier, which every
+                // wave reaches only after reading this half.
+                __syncthreads();
+                D2 Gs[NC];
+#pragma unroll
+                for (int i = 0; i < NC; ++i) Gs[i] = G[i];
+#pragma unroll
+                for (int v = 0; v < kMidWaves; ++v) {
+#pragma unroll
+                    for (int i = 0; i < NC; ++i) {
+                        if ((uint32_t)v == w) Gs[i] = G[i];  // accumulator before this wave's first update
+                        G[i].x += s_part[buf][v][i][0][lane];
+                        G[i].y += s_part[buf][v][i][1][lane];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < T; ++u) {
+                    if ((uint32_t)u < cnt) {
+#pragma unroll
+                        for (int i = 0; i < NC; ++i) item2<kAdagradSeq>(Gs[i], acc[i], g[u][i], rp);
+                    }
+                }
+            }
+            // the waves' step sums, added in the order of the waves
+#pragma unroll
+            for (int i = 0; i < NC; ++i) {
+                s_part[buf][w][i][0][lane] = acc[i].x;
+                s_part[buf][w][i][1][lane] = acc[i].y;
+            }
+            __syncthreads();
+            if (w == 0) {
+                const rsrc_t r0 = row_f64(long_res, (size_t)slot * 2 + 0, D, col0);
+                const rsrc_t r1 = row_f64(long_res, (size_t)slot * 2 + 1, D, col0);
+#pragma unroll
+                for (int i = 0; i < NC; ++i) {
+                    D2 tot = D2{0, 0};
+#pragma unroll
+                    for (int v = 0; v < kMidWaves; ++v) {
+                        tot.x += s_part[buf][v][i][0][lane];
+                        tot.y += s_part[buf][v][i][1][lane];
+                    }
+                    std2(r0, i, tot);
+                    std2(r1, i, G[i]);
+                }
+            }
+            __syncthreads();                                 // s_part is free for the next run
         }
     }
 }
@@ -1075,10 +1229,10 @@ __global__ __launch_bounds__(256) void route_kernel(const uint64_t *keys, uint64
 // kernels are launched with exactly that many, so that every block starts at time zero.  0 = the
 // occupancy query failed.
 template <typename K>
-static int resident_grid(K kernel, int cus)
+static int resident_grid(K kernel, int cus, int threads = 256)
 {
     int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess || per_cu < 1) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu < 1) return 0;
     return cus * per_cu;
 }
 
@@ -1087,6 +1241,7 @@ static bool grids_for(int cus, LaunchGrids *out)
 {
     out->p1 = resident_grid(long_piece_kernel<NC, false, MODE>, cus);
     out->p3 = resident_grid(long_piece_kernel<NC, true, MODE>, cus);
+    out->mid = resident_grid(mid_chain_kernel<NC>, cus, kMidWaves * kWave);
     if (NC == 1) {
         out->apply = resident_grid(apply_stripes_kernel_d128<MODE>, cus);
         out->rows = resident_grid(apply_rows_kernel_d128<MODE>, cus);
@@ -1094,7 +1249,8 @@ static bool grids_for(int cus, LaunchGrids *out)
         out->apply = resident_grid(apply_stripes_kernel_d256<MODE>, cus);
         out->rows = resident_grid(apply_rows_kernel_d256<MODE>, cus);
     }
-    return out->p1 > 0 && out->p3 > 0 && out->apply > 0 && out->rows > 0;
+    out->mid_min_rows = kMidMinRowsPerBlock * (uint32_t)(out->mid > 0 ? out->mid : 0);
+    return out->p1 > 0 && out->p3 > 0 && out->mid > 0 && out->apply > 0 && out->rows > 0;
 }
 
 template <int NC, int MODE>
@@ -1104,8 +1260,12 @@ static void chains_for(const Scratch &s, const Geometry &g, const LaunchGrids &l
 {
     const dim3 grid(cus * 8), block(256);
     hipLaunchKernelGGL(long_find_kernel, grid, block, 0, st, sk, n, s.hdr, s.long_slot, s.long_head, max_slots);
+    const uint32_t mid_max = MODE == kAdagradSeq ? kMidMax : 0u;     // the other rules read a long run once anyway
     hipLaunchKernelGGL(long_plan_kernel, grid, block, 0, st, sk, n, s.hdr, s.long_head, s.long_len, s.long_piece,
-                       s.long_count, s.long_base, s.piece_slot, max_slots, max_pieces);
+                       s.long_count, s.long_base, s.piece_slot, s.mid_list, mid_max, lg.mid_min_rows, max_slots, max_pieces);
+    if (mid_max > kLongRun)
+        hipLaunchKernelGGL((mid_chain_kernel<NC>), dim3(lg.mid), dim3(kMidWaves * kWave), 0, st, sk, si, grads, A, s.hdr,
+                           s.long_head, s.long_len, s.mid_list, s.long_res, max_slots, g);
     hipLaunchKernelGGL((long_piece_kernel<NC, false, MODE>), dim3(lg.p1), block, 0, st, si, grads, s.hdr, s.long_head,
                        s.long_len, s.long_piece, s.long_base, s.piece_slot, s.partial, s.partial2, max_pieces, g);
     if (!Rule<MODE>::combine) {

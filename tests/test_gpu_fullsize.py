@@ -137,7 +137,10 @@ def test_full_size(name, D, K, S, nbatch):
         sg_ = g[ssel].cpu().numpy()
         oracle.update(sE, sA, sPE, sPA, K, S, si.DEFAULT_LR, si.DEFAULT_EPS, sk_, sg_,
                       threads=min(16, oracle.max_threads()))
-        log(f"  batch {b}: {len(ck)} sampled items, {len(sk_)} shard items, stats {ctx.batch_stats()}")
+        stats = ctx.batch_stats()
+        log(f"  batch {b}: {len(ck)} sampled items, {len(sk_)} shard items, stats {stats}")
+        if name == "large_skewed":     # thousands of long rows: those of moderate length are walked by one workgroup each
+            assert stats["one_workgroup_rows"] > 3000 and stats["pieces"] > 0
         del g, gk, pos, sel, ssel, sg_
     assert ctx.status() == 0
 

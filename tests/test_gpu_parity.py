@@ -12,6 +12,8 @@ from ecrm_case import Case, grads_for, log
 pytestmark = pytest.mark.gpu
 
 LONG_RUN = 1024      # ECRM_LONG_RUN of include/ecrm.h
+MID_RUN = 32768      # ECRM_MID_RUN
+TUNE_MID_MIN_ROWS = 1
 
 
 def test_generator_matches_on_device():
@@ -83,22 +85,30 @@ def test_shapes(R, D, k, S, n):
     c.check_invariant()
 
 
-@pytest.mark.parametrize("m", [1, 2, 255, 256, 257, 1023, 1024, 1025, 1026, 5000, 300000])
-def test_one_hot_row(m):
+@pytest.mark.parametrize("one_workgroup", [False, True])
+@pytest.mark.parametrize("m", [1, 2, 255, 256, 257, 1023, 1024, 1025, 1026, 1280, 1281, 5000, 32768, 32769, 300000])
+def test_one_hot_row(m, one_workgroup):
     """All updates on one entry: the run goes through the split-chain path once it is longer than
-    1024 (the two lengths around the threshold take different paths and must agree with the oracle)."""
+    1024 (the two lengths around the threshold take different paths and must agree with the oracle).  Up to 32768
+    updates the run can be walked by one workgroup; a batch with a single long row does that only when told to."""
+    if one_workgroup and not LONG_RUN < m <= 2 * MID_RUN:
+        pytest.skip("the same path as without")
     R, D, k, S = 1 << 10, 128, 4, 5
     c = Case(R, D, k, S, max_batch=m, seed=23)
+    if one_workgroup:
+        c.ctx.tune(TUNE_MID_MIN_ROWS, 1)
     keys = np.full(m, 777, np.uint64)
     c.update(keys, grads_for(23, 0, m, D))
     stats = c.ctx.batch_stats()
     assert stats["long_rows"] == (1 if m > LONG_RUN else 0)
     assert stats["long_items"] == (m if m > LONG_RUN else 0)
+    assert stats["one_workgroup_rows"] == (1 if one_workgroup and LONG_RUN < m <= MID_RUN else 0)
     log("hot row", m, stats, c.compare(f"hot{m}"))
     c.check_invariant()
 
 
-def test_hot_rows_share_a_stripe():
+@pytest.mark.parametrize("one_workgroup", [False, True])
+def test_hot_rows_share_a_stripe(one_workgroup):
     """Two long runs and one short run in the same stripe, plus a long run at the very end."""
     R, D, k, S = 64, 128, 4, 5
     rng = np.random.default_rng(0)
@@ -106,10 +116,42 @@ def test_hot_rows_share_a_stripe():
                            rng.integers(0, R, 2000)]).astype(np.uint64)
     rng.shuffle(keys)
     c = Case(R, D, k, S, max_batch=len(keys), seed=29)
+    if one_workgroup:
+        c.ctx.tune(TUNE_MID_MIN_ROWS, 1)
     c.update(keys, grads_for(29, 0, len(keys), D))
     stats = c.ctx.batch_stats()
-    assert stats["long_rows"] == 3
+    assert stats["long_rows"] == 3 and stats["one_workgroup_rows"] == (3 if one_workgroup else 0)
     log("shared stripe", stats, c.compare("shared"))
+    c.check_invariant()
+
+
+@pytest.mark.parametrize("one_workgroup", [True, False])
+@pytest.mark.parametrize("D,k,S", [(128, 4, 5), (256, 2, 5), (36, 10, 11), (512, 4, 5)])
+def test_rows_of_every_length_class(D, k, S, one_workgroup):
+    """Runs on both sides of every boundary of the split-chain path in one batch: the 1024 above which a run
+    leaves the apply kernel, the lengths that one workgroup walks with one read of the gradients (up to 32768,
+    listed in classes that double in length, 256 or 128 updates per round), and beyond that the pieces.  A batch
+    with this few long rows would cut all of them into pieces; the tuning knob sends them to the workgroups."""
+    lens = [1024, 1025, 1279, 1281, 2048, 2049, 3000, 4096, 4097, 8192, 8193, 9000, 16384, 16385, 20000, 32767,
+            32768, 32769, 40000]
+    R = k * 64
+    rng = np.random.default_rng(5)
+    rows = rng.permutation(R)[:len(lens)]
+    keys = np.concatenate([np.full(m, r) for m, r in zip(lens, rows)] + [rng.integers(0, R, 3000)]).astype(np.uint64)
+    rng.shuffle(keys)
+    c = Case(R, D, k, S, max_batch=len(keys), seed=31)
+    if one_workgroup:
+        c.ctx.tune(TUNE_MID_MIN_ROWS, 1)
+    c.update(keys, grads_for(31, 0, len(keys), D))
+    stats = c.ctx.batch_stats()
+    counts = np.bincount(keys.astype(np.int64), minlength=R)
+    assert stats["long_rows"] == int((counts > LONG_RUN).sum())
+    assert stats["long_items"] == int(counts[counts > LONG_RUN].sum())
+    assert stats["one_workgroup_rows"] == (int(((counts > LONG_RUN) & (counts <= MID_RUN)).sum()) if one_workgroup else 0)
+    log("length classes", (D, k, S), stats, c.compare(f"classes D={D}"))
+    c.check_invariant()
+    c.update(keys[::-1].copy(), grads_for(31, len(keys), len(keys), D))      # once more, on accumulators that are not small
+    log("length classes, second call", (D, k, S), c.compare(f"classes D={D} again"))
     c.check_invariant()
 
 
