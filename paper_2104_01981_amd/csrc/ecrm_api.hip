@@ -14,7 +14,7 @@ struct Layout {
     uint32_t max_batch, max_slots, max_pieces, max_blocks;
     size_t bytes;
     size_t off_cnt, off_keys[2], off_vals[2], off_hist, off_bintotal, off_long_slot, off_long_meta,
-        off_piece_slot, off_partial, off_partial2, off_long_res;
+        off_piece_slot, off_partial, off_partial2, off_long_res, off_active;
 };
 
 // The caller's device arrays one update works on.
@@ -91,6 +91,7 @@ static Layout make_layout(uint32_t max_batch, uint32_t D, uint32_t S, bool has_p
     l.off_hist = take((size_t)kMaxBins * l.max_blocks * 4);
     l.off_bintotal = take(kMaxBins * 4);
     l.off_long_slot = take(n * 4);
+    l.off_active = take((n + kChunk - 1) / kChunk * 4);
     l.off_long_meta = take((size_t)(5 + kMidClasses) * l.max_slots * 4);
     l.off_piece_slot = take((size_t)l.max_pieces * 4);
     l.off_partial = take((size_t)l.max_pieces * D * sizeof(double));
@@ -113,6 +114,7 @@ static Scratch carve(const Layout &l, void *base, bool has_partial2)
     s.block_hist = (uint32_t *)(b + l.off_hist);
     s.bin_total = (uint32_t *)(b + l.off_bintotal);
     s.long_slot = (uint32_t *)(b + l.off_long_slot);
+    s.active = (uint32_t *)(b + l.off_active);
     uint32_t *meta = (uint32_t *)(b + l.off_long_meta);
     s.long_head = meta;
     s.long_len = meta + (size_t)l.max_slots;
@@ -302,6 +304,7 @@ static int run_update(ecrm_ctx *c, const Tables &t, const Scratch &s, const Layo
         launch_hold_back(s, c->geo, rv, keys, grads, n32, src, c->hb, c->buf_cur, st);
     if (ev) (void)hipEventRecord(ev[1], st);
     launch_chains(s, c->geo, lg, t.A, grads, sk, si, n32, l.max_slots, l.max_pieces, c->cus, st);
+    launch_active_groups(s, c->geo, sk, n32, st);
     if (ev) (void)hipEventRecord(ev[2], st);
     const bool diff = prop == ECRM_PROP_DIFFERENCE;
     launch_apply(s, c->geo, lg, t.E, t.A, diff ? t.PE : nullptr, diff ? t.PA : nullptr, t.load_data,
@@ -320,6 +323,7 @@ static int run_update(ecrm_ctx *c, const Tables &t, const Scratch &s, const Layo
         launch_sort(s, c->geo, rv, keys, n32, nullptr, kCallerBatch, bits, true, false, &sk, &si, st);
         if (ev) (void)hipEventRecord(ev[4], st);
         launch_chains(s, gp, lg, t.PA, grads, sk, si, n32, l.max_slots, l.max_pieces, c->cus, st);
+        launch_active_groups(s, gp, sk, n32, st);
         if (ev) (void)hipEventRecord(ev[5], st);
         launch_apply(s, gp, lg, t.PE, t.PA, nullptr, nullptr, nullptr, nullptr, grads, sk, si, n32, c->cus, st);
         if (ev) (void)hipEventRecord(ev[6], st);

@@ -66,7 +66,8 @@ struct Header {
     uint32_t bump;         // slots of the row pool that have ever been handed out
     uint32_t n_mid[kMidClasses];   // long rows of this batch that one workgroup walks, by length class
     uint32_t mid_ticket;   // next of them to be handed out (cleared by reset)
-    uint32_t pad[43];
+    uint32_t n_active;     // groups of sorted positions the apply kernel has work for (cleared by reset)
+    uint32_t pad[42];
 };
 static_assert(sizeof(Header) == 256, "header is one 256-byte block");
 
@@ -78,6 +79,7 @@ struct Scratch {           // device pointers carved out of the caller's scratch
     uint32_t *block_hist;          // [bins][nblocks]
     uint32_t *bin_total;           // [bins]
     uint32_t *long_slot;           // [n] slot id, valid at heads of long rows only
+    uint32_t *active;              // [ceil(n / kChunk)] groups of sorted positions in which a stripe begins
     uint32_t *long_head, *long_len, *long_piece, *long_count, *long_base;   // [max_slots]
     uint32_t *mid_list;            // [kMidClasses][max_slots] slots of the rows one workgroup walks
     uint32_t *piece_slot;          // [max_pieces]
@@ -198,6 +200,7 @@ void launch_hold_back(const Scratch &s, const Geometry &g, const RecoveryView &r
 void launch_recover_range(const Geometry &g, float *E, float *A, float *PE, float *PA, uint32_t server,
                           uint32_t g_lo, uint32_t g_hi, int grid_blocks, hipStream_t st);
 void launch_clear_buffer(const Scratch &s, hipStream_t st);
+void launch_active_groups(const Scratch &s, const Geometry &g, const uint32_t *sk, uint32_t n, hipStream_t st);
 void launch_chains(const Scratch &s, const Geometry &g, const LaunchGrids &lg, const float *A, const float *grads,
                    const uint32_t *sk, const uint32_t *si, uint32_t n, uint32_t max_slots,
                    uint32_t max_pieces, int cus, hipStream_t st);

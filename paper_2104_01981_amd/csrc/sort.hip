@@ -64,6 +64,7 @@ __global__ void reset_kernel(Header *h, unsigned long long *cnt, uint32_t S, uin
         h->apply_ticket = 0;
         for (uint32_t c = 0; c < kMidClasses; ++c) h->n_mid[c] = 0;
         h->mid_ticket = 0;
+        h->n_active = 0;
     }
     for (uint32_t i = t; i < 2 * S; i += blockDim.x) cnt[i] = 0;
 }

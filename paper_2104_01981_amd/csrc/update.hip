@@ -681,10 +681,91 @@ __global__ __launch_bounds__(kMidWaves * kWave, 4) void mid_chain_kernel(
 // apply
 // ================================================================================================
 
+constexpr uint32_t kGroupsPerTicket = 8;
+constexpr int kListThreads = 256;
+constexpr uint32_t kListMaxTiles = 4;
+
+// Lists the groups of kChunk sorted positions in which a stripe begins: the groups the apply kernel has work
+// for.  All others lie inside runs -- every group of a long row's positions but its first -- and while
+// they were handed out like the rest, the waves went through such a stretch at the pace of the ticket counter,
+// a few nanoseconds per ticket with nothing done (1.2 of 8.4 ms on a Zipf batch).  A block looks at `tiles`
+// tiles of kListThreads groups: a tile's positions are read coalesced, all loads of a thread in flight
+// together, and their stripe numbers staged in LDS; a position whose stripe differs from its left neighbour's
+// marks its group; the marked groups are appended to the list with one counter update per block (the list
+// ascends inside a block's part; the order of the parts does not matter).
+__global__ __launch_bounds__(kListThreads) void active_groups_kernel(const uint32_t *sk, uint32_t n, Header *hdr,
+                                                                     Divider dk, uint32_t tiles, uint32_t *active)
+{
+    constexpr uint32_t kTilePos = kListThreads * kChunk;                   // positions of a tile
+    constexpr uint32_t kNone = 0xFFFFFFFFu, kEdge = 0xFFFFFFFEu;           // no stripe has these numbers
+    __shared__ uint32_t s_q[1 + kTilePos];                                 // [0]: the position left of the tile
+    __shared__ uint32_t s_mark[kListMaxTiles][kListThreads];
+    __shared__ uint32_t s_cnt[kListMaxTiles][kListThreads / kWave];
+    __shared__ uint32_t s_base;
+    if (hdr->batch_bad) return;
+    n = min(n, hdr->n_valid);
+    const uint32_t tid = threadIdx.x, lane = lane_id(), w = tid / kWave;
+    const uint32_t g0 = blockIdx.x * tiles * (uint32_t)kListThreads;       // the block's first group
+    for (uint32_t t = 0; t < tiles; ++t) {
+        const uint32_t p_lo = (g0 + t * (uint32_t)kListThreads) * kChunk;  // < n + 2^16: no overflow, n <= 2^31
+        uint32_t key[kChunk];
+#pragma unroll
+        for (uint32_t i = 0; i < kChunk; ++i) {
+            const uint32_t p = p_lo + i * (uint32_t)kListThreads + tid;
+            key[i] = p < n ? sk[p] : kNone;
+        }
+        if (tid == 0) s_q[0] = (p_lo > 0 && p_lo <= n) ? dk.div(sk[p_lo - 1]) : kEdge;
+#pragma unroll
+        for (uint32_t i = 0; i < kChunk; ++i)
+            s_q[1 + i * (uint32_t)kListThreads + tid] = key[i] == kNone ? kNone : dk.div(key[i]);
+        s_mark[t][tid] = 0;
+        __syncthreads();
+#pragma unroll
+        for (uint32_t i = 0; i < kChunk; ++i) {
+            const uint32_t rel = i * (uint32_t)kListThreads + tid;
+            const uint32_t q = s_q[1 + rel];
+            if (q != kNone && q != s_q[rel]) s_mark[t][rel / kChunk] = 1u;  // every writer writes 1
+        }
+        __syncthreads();                                                   // s_q is free for the next tile
+    }
+    // compaction of the block's marks: per wave and tile a count, then one place in the list for the block
+    uint32_t mine_mask = 0;                                                // bit t: group (t, tid) is marked
+    for (uint32_t t = 0; t < tiles; ++t) {
+        const bool mine = s_mark[t][tid] != 0;
+        const unsigned long long bal = __ballot(mine);
+        if (mine) mine_mask |= 1u << t;
+        if (lane == 0) s_cnt[t][w] = (uint32_t)__popcll(bal);
+    }
+    __syncthreads();
+    uint32_t total = 0, before[kListMaxTiles];
+#pragma unroll
+    for (uint32_t t = 0; t < kListMaxTiles; ++t) {
+        before[t] = 0;
+        if (t < tiles) {
+#pragma unroll
+            for (int v = 0; v < kListThreads / kWave; ++v) {
+                const uint32_t c = s_cnt[t][v];
+                if ((uint32_t)v == w) before[t] = total;
+                total += c;
+            }
+        }
+    }
+    if (tid == 0) s_base = total ? atomicAdd(&hdr->n_active, total) : 0u;
+    __syncthreads();
+#pragma unroll
+    for (uint32_t t = 0; t < kListMaxTiles; ++t) {
+        const bool mine = (mine_mask >> t) & 1u;                           // never set for t >= tiles
+        const unsigned long long bal = __ballot(mine);
+        if (mine) active[s_base + before[t] + (uint32_t)__popcll(bal & bits_below(lane))] = g0 + t * (uint32_t)kListThreads + tid;
+    }
+}
+
 struct ApplyArgs {
     float *E, *A, *PE, *PA;
     const float *grads;
     const uint32_t *sk, *si;
+    const uint32_t *active;      // groups of kChunk sorted positions in which a stripe begins (hdr->n_active of them);
+                                 // null: no list was made, every group is looked at
     const uint32_t *long_slot, *long_len;
     const double *long_res;
     Header *hdr;
@@ -973,66 +1054,57 @@ __device__ __forceinline__ void apply_stripes_body(const ApplyArgs &a)
         }
     }
     const uint32_t n = min(a.n, a.hdr->n_valid), k = a.geo.k, lane = lane_id();
-    const uint32_t nchunks = (n + kChunk - 1) / kChunk;
-    // Groups of sorted positions are handed out through a counter instead of by a fixed stride: the
-    // work per group varies (runs, long stripes), and with a fixed stride the slowest wave set the
-    // kernel's time (6.50 -> 6.22 ms).  One ticket covers ECRM_APPLY_DYNAMIC groups: one ticket per
-    // group made the counter itself the bottleneck (12.5 ms), 64 per ticket is too coarse again.
-#ifndef ECRM_APPLY_DYNAMIC
-#define ECRM_APPLY_DYNAMIC 8
-#endif
-#if ECRM_APPLY_DYNAMIC
-    // a wave's first ticket is its own number (no counter traffic at start-up, which is all a small
-    // batch consists of); later ones come from the counter.  Small batches get smaller tickets, so
-    // that every wave has work.
-    const uint32_t per_ticket = min((uint32_t)ECRM_APPLY_DYNAMIC, max(1u, nchunks / (4u * wave_count())));
-    uint32_t ch = wave_id() * per_ticket, left = per_ticket;
-#ifndef ECRM_KEY_PREFETCH
-#define ECRM_KEY_PREFETCH 1
-#endif
-#if ECRM_KEY_PREFETCH
+    // The groups of kChunk sorted positions in which a stripe begins (active_groups_kernel lists them) are handed
+    // out through a counter instead of by a fixed stride: the work per group varies (runs, long stripes), and
+    // with a fixed stride the slowest wave set the kernel's time (6.50 -> 6.22 ms).  One ticket covers
+    // kGroupsPerTicket listed groups: one group per ticket made the counter itself the bottleneck (12.5 ms), 64
+    // per ticket is too coarse again.  A wave's first ticket is its own number (no counter traffic at start-up,
+    // which is all a small batch consists of); later ones come from the counter.  Small batches get smaller
+    // tickets, so that every wave has work.
+    const uint32_t ngroups = (n + kChunk - 1) / kChunk;
+    const uint32_t nact = a.active ? min(a.hdr->n_active, ngroups) : ngroups;   // no list (a small batch): every group
+    const uint32_t per_ticket = min(kGroupsPerTicket, max(1u, nact / (4u * wave_count())));
+    const bool one_ticket_each = (nact + per_ticket - 1) / per_ticket <= wave_count();
+    uint32_t at = wave_id() * per_ticket;              // the ticket's place in the list
+    uint32_t left = 0, taken = 0, listed = 0;          // groups left in the ticket, taken from it; lane i: its group i
     uint32_t pf_ch = 0xFFFFFFFFu, pf_key = 0, pf_idx = 0, pf_prev = 0;
-#endif
-    for (;; ++ch) {
+    for (bool first_ticket = true;;) {
         if (left == 0) {
-            // every ticket was a first ticket: nothing to fetch (and no counter traffic for small batches)
-            if ((nchunks + per_ticket - 1) / per_ticket <= wave_count()) break;
-            uint32_t t = 0;
-            if (lane == 0) t = atomicAdd(&a.hdr->apply_ticket, 1u);
-            ch = (wave_count() + uniform(t)) * per_ticket;
-            left = per_ticket;
+            if (!first_ticket) {
+                if (one_ticket_each) break;
+                uint32_t t = 0;
+                if (lane == 0) t = atomicAdd(&a.hdr->apply_ticket, 1u);
+                at = (wave_count() + uniform(t)) * per_ticket;
+            }
+            first_ticket = false;
+            if (at >= nact) break;
+            left = min(per_ticket, nact - at);
+            listed = lane < left ? (a.active ? a.active[at + lane] : at + lane) : 0u;
+            taken = 0;
         }
+        const uint32_t ch = from_lane(listed, taken);
+        ++taken;
         --left;
-        if (ch >= nchunks) break;
-#else
-    for (uint32_t ch = wave_id(); ch < nchunks; ch += wave_count()) {
-#endif
         const uint32_t p0 = ch * kChunk;
         uint32_t wkey, widx, prevk;
-#if ECRM_KEY_PREFETCH
         // The group's 64 (row, index) pairs were asked for while the previous group was being worked on;
-        // only a ticket's first group has to wait for them.  (Without this every group began with a
-        // memory latency, also the many groups that lie inside a long run and have nothing to do.)
+        // only a ticket's first group has to wait for them.
         if (pf_ch == ch) {
             wkey = pf_key;
             widx = pf_idx;
             prevk = uniform(pf_prev);
-        } else
-#endif
-        {
+        } else {
             wkey = p0 + lane < n ? a.sk[p0 + lane] : kNoKey;
             widx = p0 + lane < n ? a.si[p0 + lane] : 0u;
             prevk = p0 ? uniform(a.sk[p0 - 1]) : kNoKey;
         }
-#if ECRM_KEY_PREFETCH
-        if (left > 0 && ch + 1 < nchunks) {
-            const uint32_t q0 = p0 + kChunk;
+        if (left > 0) {
+            pf_ch = from_lane(listed, taken);
+            const uint32_t q0 = pf_ch * kChunk;
             pf_key = q0 + lane < n ? a.sk[q0 + lane] : kNoKey;
             pf_idx = q0 + lane < n ? a.si[q0 + lane] : 0u;
-            pf_prev = a.sk[q0 - 1];
-            pf_ch = ch + 1;
+            pf_prev = q0 ? a.sk[q0 - 1] : kNoKey;
         }
-#endif
         uint32_t leftk = __shfl_up(wkey, 1, kWave);
         if (lane == 0) leftk = prevk;
         const bool valid = wkey != kNoKey;
@@ -1263,7 +1335,7 @@ static void chains_for(const Scratch &s, const Geometry &g, const LaunchGrids &l
     const uint32_t mid_max = MODE == kAdagradSeq ? kMidMax : 0u;     // the other rules read a long run once anyway
     hipLaunchKernelGGL(long_plan_kernel, grid, block, 0, st, sk, n, s.hdr, s.long_head, s.long_len, s.long_piece,
                        s.long_count, s.long_base, s.piece_slot, s.mid_list, mid_max, lg.mid_min_rows, max_slots, max_pieces);
-    if (mid_max > kLongRun)
+    if (mid_max > kLongRun && n / (kLongRun + 1u) >= lg.mid_min_rows)       // else the plan kernel lists no such run
         hipLaunchKernelGGL((mid_chain_kernel<NC>), dim3(lg.mid), dim3(kMidWaves * kWave), 0, st, sk, si, grads, A, s.hdr,
                            s.long_head, s.long_len, s.mid_list, s.long_res, max_slots, g);
     hipLaunchKernelGGL((long_piece_kernel<NC, false, MODE>), dim3(lg.p1), block, 0, st, si, grads, s.hdr, s.long_head,
@@ -1326,6 +1398,21 @@ void launch_chains(const Scratch &s, const Geometry &g, const LaunchGrids &lg, c
     ECRM_DISPATCH(chains_for, s, g, lg, A, grads, sk, si, n, max_slots, max_pieces, cus, st);
 }
 
+// A batch this small is one wave's ticket or two per wave anyway: the list would cost a launch and save nothing.
+static bool lists_groups(uint32_t n) { return n > (1u << 18); }
+
+// the list of groups launch_apply works from; n > 0
+void launch_active_groups(const Scratch &s, const Geometry &g, const uint32_t *sk, uint32_t n, hipStream_t st)
+{
+    if (!lists_groups(n)) return;
+    const uint32_t groups = (n + kChunk - 1) / kChunk;
+    // a large batch: several tiles per block, so that the list's counter is not updated at its own pace
+    const uint32_t tiles = groups > 64u * kListThreads ? kListMaxTiles : 1u;
+    const uint32_t per_block = tiles * kListThreads;
+    hipLaunchKernelGGL(active_groups_kernel, dim3((groups + per_block - 1) / per_block), dim3(kListThreads), 0, st, sk, n,
+                       s.hdr, make_divider(g.k), tiles, s.active);
+}
+
 void launch_apply(const Scratch &s, const Geometry &g, const LaunchGrids &lg, float *E, float *A, float *PE, float *PA,
                   unsigned long long *load_data, unsigned long long *load_parity, const float *grads,
                   const uint32_t *sk, const uint32_t *si, uint32_t n, int cus, hipStream_t st)
@@ -1335,6 +1422,7 @@ void launch_apply(const Scratch &s, const Geometry &g, const LaunchGrids &lg, fl
     a.E = E; a.A = A; a.PE = PE; a.PA = PA;
     a.grads = grads; a.sk = sk; a.si = si;
     a.long_slot = s.long_slot; a.long_len = s.long_len; a.long_res = s.long_res;
+    a.active = lists_groups(n) ? s.active : nullptr;
     a.hdr = s.hdr; a.cnt = s.cnt;
     a.load_data = load_data; a.load_parity = load_parity;
     a.n = n; a.geo = g;

@@ -133,7 +133,7 @@ def test_rows_of_every_length_class(D, k, S, one_workgroup):
     listed in classes that double in length, 256 or 128 updates per round), and beyond that the pieces.  A batch
     with this few long rows would cut all of them into pieces; the tuning knob sends them to the workgroups."""
     lens = [1024, 1025, 1279, 1281, 2048, 2049, 3000, 4096, 4097, 8192, 8193, 9000, 16384, 16385, 20000, 32767,
-            32768, 32769, 40000]
+            32768, 32769, 40000, 50000]     # more than 2^18 updates in all: the apply kernel works from its list of groups
     R = k * 64
     rng = np.random.default_rng(5)
     rows = rng.permutation(R)[:len(lens)]
