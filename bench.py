@@ -27,9 +27,9 @@ LONG_RUN = 1024          # ECRM_LONG_RUN of include/ecrm.h: longer runs leave th
 # HBM bytes per launch of the apply kernel, from rocprofv3 FETCH_SIZE and WRITE_SIZE scaled by a plain copy of known
 # size (profiles/update_path_<workload>_hbm_traffic.txt).  Reported only while the code of the kernel's sources is
 # what the counters were taken on.
-TRAFFIC_BYTES_PER_LAUNCH = {"hbm_scale": 38002218916, "large_uniform": 77525602221, "large_skewed": 43075325362}
+TRAFFIC_BYTES_PER_LAUNCH = {"hbm_scale": 37955942900, "large_uniform": 77511042063, "large_skewed": 42549874599}
 TRAFFIC_SOURCES = ["paper_2104_01981_amd/csrc/update.hip", "paper_2104_01981_amd/csrc/ecrm_internal.h"]
-TRAFFIC_SOURCES_SHA256 = "39e7ef2c97bbaabbc6036ff3c93bde0b97b3c7be1da1b2dc97674eebe0d38dd8"
+TRAFFIC_SOURCES_SHA256 = "df88726dedee22b1aec2cfce42752f15790efd1bec5c1c14a1029e0c1605a06d"
 
 
 def code_digest(paths):
@@ -267,13 +267,13 @@ def main():
         Up = int(torch.unique(uk // k).numel())
         n_long = int(cnt[cnt > LONG_RUN].sum())
         if prop == 2:        # no parities
-            return per * (8 + 4 * D) + U * 16 * D, per * 8 + (per - n_long) * 4 * D + U * 16 * D
+            return per * (8 + 4 * D) + U * 16 * D, (per - n_long) * (8 + 4 * D) + U * 16 * D
         if prop == 1:        # every gradient goes to two servers; the two apply launches together
             _, pcnt = torch.unique(kt // k, return_counts=True)
             n_long_p = int(pcnt[pcnt > LONG_RUN].sum())
             return (2 * per * (8 + 4 * D) + (U + Up) * 16 * D,
-                    2 * per * 8 + (2 * per - n_long - n_long_p) * 4 * D + (U + Up) * 16 * D)
-        return per * (8 + 4 * D) + (U + Up) * 16 * D, per * 8 + (per - n_long) * 4 * D + (U + Up) * 16 * D
+                    (2 * per - n_long - n_long_p) * (8 + 4 * D) + (U + Up) * 16 * D)
+        return per * (8 + 4 * D) + (U + Up) * 16 * D, (per - n_long) * (8 + 4 * D) + (U + Up) * 16 * D
 
     # Physical placement is the driver's; the same kernel on the same data runs at 0.75 or at 0.63 of the
     # HBM peak depending on where the four tables lie relative to each other (rocprofv3 counters: same
