@@ -59,20 +59,25 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def _timed(torch, fn, reps=5):
+    """seconds per call of fn (device time between two events on the current stream), after one untimed call"""
+    fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps * 1e-3
+
+
 def memory_ceilings(torch, dev):
     """Rates of the plainest memory-bound kernels on this device, in GB/s of bytes read plus bytes written:
     an 8 GiB device-to-device copy; a gather of random 512-byte rows out of an 8 GiB table; and the
     read-modify-write of such rows (gather, then scatter back), which is the access pattern of the
     update path's tables."""
     def timed(fn, reps=5):
-        fn()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps * 1e-3
+        return _timed(torch, fn, reps)
     rows, width = 1 << 24, 128                                    # 8 GiB of 512-byte rows
     src = torch.zeros(rows, width, device=dev)
     dst = torch.empty_like(src)
@@ -97,6 +102,44 @@ def memory_ceilings(torch, dev):
     del src, dst, buf, idx
     torch.cuda.empty_cache()
     return res
+
+
+def row_traffic_by_distance(torch, dev):
+    """The tables' own access pattern -- whole 512-byte rows at random row numbers, eight in flight per wavefront
+    (the library's probe kernel) -- on two 8 GiB tables inside one allocation, as a function of how far apart they
+    lie: read only, and read + written back.  GB/s of bytes read plus bytes written.  Meant for a process that holds
+    no other device memory (bench.py runs it in a child process before it touches the device itself)."""
+    from paper_2104_01981_amd import probe_row_traffic
+    GiB, table_rows, n = 1 << 30, 1 << 24, 1 << 23
+    arena = None
+    for span in (200, 136, 72):                                   # GiB; the largest one the memory allows
+        try:
+            arena = torch.empty(span * GiB, dtype=torch.uint8, device=dev)
+            break
+        except RuntimeError:
+            arena = None
+    if arena is None:
+        return None
+    arena.zero_()
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    rows = torch.randint(0, table_rows, (n,), device=dev, generator=gen, dtype=torch.int32)
+    sink = torch.zeros(1, device=dev)
+    out = {"what": "2^23 random rows of 128 floats, alternately from two 8 GiB tables that start this many GiB apart "
+                   "inside one allocation (the first at its start), in a process that holds nothing else; read only / "
+                   "read and written back; bytes read + written per second",
+           "allocation_GiB": span,
+           "read_GBps": {}, "read_write_GBps": {}}
+    for dist in (8, 32, 56, 64, 72, 128):
+        if dist + 8 > span:
+            continue
+        ta, tb = arena[:8 * GiB], arena[dist * GiB:(dist + 8) * GiB]
+        for write, key in ((0, "read_GBps"), (1, "read_write_GBps")):
+            secs = _timed(torch, lambda: probe_row_traffic(ta, tb, table_rows, rows, write, sink))
+            out[key][str(dist)] = n * 512 * (2 if write else 1) / secs / 1e9
+    del arena, rows, sink
+    torch.cuda.empty_cache()
+    return out
 
 
 def main():
@@ -143,6 +186,9 @@ def main():
     ap.add_argument("--first-geometry", type=int, default=0, help="index of the geometry the first trial uses")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain device-to-device copies of 8 GiB (to scale rocprof's HBM byte counters)")
+    ap.add_argument("--row-traffic", type=int, default=1,
+                    help="0: leave out the row-traffic-by-distance figures (a child process, run first)")
+    ap.add_argument("--row-traffic-child", action="store_true", help="only measure those figures and print them")
     ap.add_argument("--per-step", action="store_true",
                     help="diagnostic: after the timed region, run the steps again one by one and log each one's phases")
     args = ap.parse_args()
@@ -150,6 +196,20 @@ def main():
         log("bench.py: this library runs on ONE GPU (all servers' shards in one HBM); "
             "--gpus must be 1, no multi-GPU figure exists.")
         sys.exit(2)
+
+    # What the device's memory delivers for the tables' access pattern, by distance between two tables: measured
+    # by a child process of its own BEFORE this one touches the device, so that it has the device memory to itself
+    # and leaves nothing behind.
+    row_traffic = json.loads(os.environ.get("ECRM_BENCH_ROW_TRAFFIC", "null"))
+    if (args.row_traffic and not args.no_ceilings and not args.row_traffic_child and not args.calibrate_copy
+            and row_traffic is None):
+        import subprocess
+        try:
+            child = subprocess.run([sys.executable, os.path.abspath(__file__), "--row-traffic-child"],
+                                   capture_output=True, text=True, timeout=300)
+            row_traffic = json.loads(child.stdout.strip().splitlines()[-1]) if child.returncode == 0 else None
+        except (subprocess.TimeoutExpired, ValueError, IndexError):
+            row_traffic = None
 
     import numpy as np
     import torch
@@ -164,6 +224,9 @@ def main():
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.row_traffic_child:
+        print(json.dumps(row_traffic_by_distance(torch, dev)), flush=True)
+        return
     if args.calibrate_copy:
         src = torch.zeros(1 << 31, dtype=torch.float32, device=dev)      # 8 GiB
         dst = torch.empty_like(src)
@@ -345,7 +408,8 @@ def main():
         argv = [a for a in sys.argv[1:]]
         rc = subprocess.call([sys.executable, os.path.abspath(__file__), *argv, "--fresh-process-retry", "0",
                               "--first-geometry", str(args.first_geometry + len(placement))],
-                             env=dict(os.environ, ECRM_BENCH_PARENT_PROBES=json.dumps(placement)))
+                             env=dict(os.environ, ECRM_BENCH_PARENT_PROBES=json.dumps(placement),
+                                      ECRM_BENCH_ROW_TRAFFIC=json.dumps(row_traffic)))
         sys.exit(rc)
     fill_tables()                                  # the probe's updates are undone: tables start from the recipe
 
@@ -545,6 +609,7 @@ def main():
     #      measured after the timed region, on memory of its own)
     if not args.no_ceilings:
         out["ceilings"] = memory_ceilings(torch, dev)
+        out["ceilings"]["row_traffic_by_distance"] = row_traffic
 
     # ---- the same update with one plain allocation per array, as a caller who does not arrange the tables
     #      would have it (the arena above is this benchmark's own arrangement)

@@ -251,11 +251,20 @@ int ecrm_clear_status(ecrm_ctx *ctx, void *hip_stream);
  * chunks of which `next_chunk` are rebuilt and the next one is locked or not, out[4] = 1 if an update
  * to `key` would be held back (Sec. 3.4) and out[5] = the unit of its stripe that the failed server
  * holds (member index, k for the parity, 0xFFFFFFFF for none).  EINVAL for key >= rows, a bad server
- * or chunk count. */
+ * or chunk count.
+ * ecrm_probe_row_traffic needs no context: it enqueues one kernel that reads `n` rows of 128 floats, alternately
+ * from table_a and table_b (device, 8-byte aligned, table_rows rows each), at the row numbers rows[i] (device;
+ * the caller keeps them below table_rows -- they are not checked), eight rows in flight per wavefront, and, if
+ * `write` is not 0, writes every row back with 1 added -- the access pattern of the update path's tables, for a
+ * benchmark that wants to know what the device's memory delivers for it depending on where two tables lie.
+ * sink: one device float (only ever written if a sum of loaded values hits a magic number).  A tail of n mod 8
+ * rows is left out.  EINVAL for null pointers, n = 0 or n >= 2^32. */
 enum { ECRM_PHASE_GROUP = 0, ECRM_PHASE_CHAINS = 1, ECRM_PHASE_APPLY = 2, ECRM_PHASES = 3 };
 enum { ECRM_PROFILE_MAX_CALLS = 256, ECRM_LONG_RUN = 1024, ECRM_MID_RUN = 32768 };
 enum { ECRM_TUNE_MID_MIN_ROWS = 1 };
 int ecrm_tune(ecrm_ctx *ctx, int what, uint64_t value);
+int ecrm_probe_row_traffic(float *table_a, float *table_b, uint64_t table_rows, const uint32_t *rows, uint64_t n,
+                           int write, float *sink, void *hip_stream);
 int ecrm_profile(ecrm_ctx *ctx, int enable);
 int ecrm_profile_read(ecrm_ctx *ctx, double *ms, uint64_t *calls);
 int ecrm_batch_stats(ecrm_ctx *ctx, void *hip_stream, uint64_t *out);

@@ -19,7 +19,7 @@ _lib = None
 
 SYMBOLS = ["ecrm_create", "ecrm_destroy", "ecrm_data_bytes", "ecrm_parity_bytes", "ecrm_scratch_bytes",
            "ecrm_bind", "ecrm_encode", "ecrm_route", "ecrm_update", "ecrm_update_static", "ecrm_status", "ecrm_clear_status",
-           "ecrm_tune", "ecrm_profile", "ecrm_profile_read", "ecrm_batch_stats", "ecrm_host_placement", "ecrm_strerror",
+           "ecrm_tune", "ecrm_probe_row_traffic", "ecrm_profile", "ecrm_profile_read", "ecrm_batch_stats", "ecrm_host_placement", "ecrm_strerror",
            "ecrm_fail_server", "ecrm_recover_server", "ecrm_degraded_read",
            "ecrm_recovery_begin", "ecrm_recovery_lock", "ecrm_recovery_decode", "ecrm_recovery_unlock",
            "ecrm_recovery_state", "ecrm_recovery_read"]
@@ -73,6 +73,7 @@ def load_library():
         lib.ecrm_status.argtypes = [vp, vp]
         lib.ecrm_clear_status.argtypes = [vp, vp]
         lib.ecrm_tune.argtypes = [vp, C.c_int, C.c_uint64]
+        lib.ecrm_probe_row_traffic.argtypes = [vp, vp, C.c_uint64, vp, C.c_uint64, C.c_int, vp, vp]
         lib.ecrm_profile.argtypes = [vp, C.c_int]
         lib.ecrm_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
         lib.ecrm_batch_stats.argtypes = [vp, vp, C.POINTER(C.c_uint64)]
@@ -96,6 +97,15 @@ def _stream(stream):
     import torch
     s = stream if stream is not None else torch.cuda.current_stream()
     return C.c_void_p(s.cuda_stream)
+
+
+def probe_row_traffic(table_a, table_b, table_rows, rows, write, sink, stream=None):
+    """ecrm_probe_row_traffic (measurement aid): rows of 128 floats at rows[i], alternately from the two tables."""
+    rc = load_library().ecrm_probe_row_traffic(_ptr(table_a), _ptr(table_b), C.c_uint64(table_rows), _ptr(rows),
+                                               C.c_uint64(rows.numel()), C.c_int(1 if write else 0), _ptr(sink),
+                                               _stream(stream))
+    if rc != ECRM_OK:
+        raise EcrmError(rc, "ecrm_probe_row_traffic")
 
 
 class Ecrm:

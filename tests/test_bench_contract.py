@@ -18,6 +18,8 @@ def test_more_than_one_gpu_is_refused():
 @pytest.mark.gpu
 @pytest.mark.parametrize("extra", [[], ["--graph"], ["--optimizer", "momentum", "--combine"], ["--propagation", "gradient"]])
 def test_bench_line_on_the_small_workload(extra):
+    if extra:
+        extra = [*extra, "--row-traffic", "0"]         # the child process that measures those figures: once is enough
     p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "tiny", "--steps", "3",
                         "--warmup", "1", *extra], capture_output=True, text=True, timeout=600)
     assert p.returncode == 0, p.stderr[-2000:]
@@ -32,5 +34,11 @@ def test_bench_line_on_the_small_workload(extra):
     r = d["roofline"]
     assert r["bound"] == "hbm" and r["peak"] == 8000.0 and abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-12
     assert r["traffic"] is None                        # counters exist for the default workload only
+    by_distance = d["ceilings"]["row_traffic_by_distance"]
+    if extra:
+        assert by_distance is None
+    else:                                              # read-modify-write of rows never beats reading them
+        assert by_distance["read_write_GBps"] and by_distance["read_GBps"].keys() == by_distance["read_write_GBps"].keys()
+        assert all(0 < by_distance["read_write_GBps"][g] < 1.05 * by_distance["read_GBps"][g] for g in by_distance["read_GBps"])
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["value"] > 0 and c["cores"] >= 1

@@ -286,3 +286,23 @@ def test_update_inside_a_hip_graph():
     torch.cuda.synchronize()
     assert torch.equal(a.E, b.E) and torch.equal(a.PA, b.PA)
     assert a.ctx.status() == 0
+
+
+def test_row_traffic_probe():
+    """The measurement aid behind the bench line's row-traffic figures: rows at even positions of the list come from
+    the first table, rows at odd positions from the second; with `write` each of them is written back plus one."""
+    from paper_2104_01981_amd import probe_row_traffic
+    table_rows, n = 5000, 4096
+    ta = torch.zeros(table_rows, 128, device="cuda")
+    tb = torch.zeros(table_rows, 128, device="cuda")
+    rows = torch.randperm(table_rows, device="cuda")[:n].to(torch.int32)
+    sink = torch.zeros(1, device="cuda")
+    probe_row_traffic(ta, tb, table_rows, rows, 0, sink)
+    assert float(ta.abs().sum()) == 0.0 and float(tb.abs().sum()) == 0.0 and float(sink) == 0.0
+    probe_row_traffic(ta, tb, table_rows, rows, 1, sink)
+    probe_row_traffic(ta, tb, table_rows, rows, 1, sink)
+    want_a = torch.zeros(table_rows, device="cuda")
+    want_b = torch.zeros(table_rows, device="cuda")
+    want_a[rows[0::2].long()] = 2.0
+    want_b[rows[1::2].long()] = 2.0
+    assert torch.equal(ta, want_a[:, None].expand(-1, 128)) and torch.equal(tb, want_b[:, None].expand(-1, 128))
