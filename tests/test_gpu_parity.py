@@ -85,14 +85,15 @@ def test_shapes(R, D, k, S, n):
     c.check_invariant()
 
 
-@pytest.mark.parametrize("one_workgroup", [False, True])
-@pytest.mark.parametrize("m", [1, 2, 255, 256, 257, 1023, 1024, 1025, 1026, 1280, 1281, 5000, 32768, 32769, 300000])
+HOT_ROW_LENGTHS = [1, 2, 255, 256, 257, 1023, 1024, 1025, 1026, 1280, 1281, 5000, 32768, 32769, 300000]
+
+
+@pytest.mark.parametrize("m,one_workgroup", [(m, False) for m in HOT_ROW_LENGTHS] +
+                         [(m, True) for m in HOT_ROW_LENGTHS if LONG_RUN < m <= 2 * MID_RUN])
 def test_one_hot_row(m, one_workgroup):
     """All updates on one entry: the run goes through the split-chain path once it is longer than
     1024 (the two lengths around the threshold take different paths and must agree with the oracle).  Up to 32768
     updates the run can be walked by one workgroup; a batch with a single long row does that only when told to."""
-    if one_workgroup and not LONG_RUN < m <= 2 * MID_RUN:
-        pytest.skip("the same path as without")
     R, D, k, S = 1 << 10, 128, 4, 5
     c = Case(R, D, k, S, max_batch=m, seed=23)
     if one_workgroup:
