@@ -68,6 +68,19 @@ def test_unbound_context_refuses_work(lib):
     lib.ecrm_destroy(None)
 
 
+def test_tuning_knob_and_probe_validate_their_arguments(lib):
+    rc, ctx = _create(lib)
+    assert rc == 0
+    assert lib.ecrm_tune(ctx, 1, C.c_uint64(7)) == 0                       # ECRM_TUNE_MID_MIN_ROWS
+    assert lib.ecrm_tune(ctx, 1, C.c_uint64(0)) == 0                       # back to the default
+    assert lib.ecrm_tune(ctx, 1, C.c_uint64(1 << 32)) == binding.ECRM_EINVAL
+    assert lib.ecrm_tune(ctx, 99, C.c_uint64(1)) == binding.ECRM_EINVAL    # no such knob
+    assert lib.ecrm_tune(None, 1, C.c_uint64(1)) == binding.ECRM_EINVAL
+    lib.ecrm_destroy(ctx)
+    # the probe refuses null pointers and empty or oversized lists before it touches the device
+    assert lib.ecrm_probe_row_traffic(None, None, C.c_uint64(16), None, C.c_uint64(8), 0, None, None) == binding.ECRM_EINVAL
+
+
 def test_strerror(lib):
     for code in range(-6, 1):
         assert len(lib.ecrm_strerror(code)) > 1
