@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libecrm.so")
-SOURCES = ["ecrm_api.hip", "sort.hip", "update.hip", "recover.hip", "holdback.hip", "probe.hip"]
+SOURCES = ["ecrm_api.hip", "sort.hip", "update.hip", "chains.hip", "recover.hip", "holdback.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-result"]

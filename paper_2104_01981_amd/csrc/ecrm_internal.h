@@ -175,6 +175,7 @@ struct LaunchGrids {
     int apply, rows;       // apply with / without the parity rows
 };
 bool query_launch_grids(const Geometry &g, int cus, LaunchGrids *out);   // false: an occupancy query failed
+bool query_chain_grids(const Geometry &g, int cus, LaunchGrids *out);    // its p1, p3, mid, mid_min_rows part
 
 // ---- launchers (each checks nothing: the API layer validates shapes before calling) -------------
 // Where a batch comes from.  kCallerBatch: n keys of the caller with gradient row i for item i.
