@@ -13,17 +13,34 @@ namespace ecrm {
 // split-chain path
 // ================================================================================================
 
-// Marks the heads of rows with more than kLongRun updates and gives each a slot.
+// Marks the heads of rows with more than kLongRun updates and gives each a slot.  Only every (kLongRun/2)-th
+// sorted position is looked at: a run of more than kLongRun positions contains two such positions in a row, q and
+// q + kLongRun/2, and exactly one q whose predecessor q - kLongRun/2 lies outside the run; the thread of that q finds
+// the run's head (binary search over the kLongRun/2 positions before q) and checks its length.  So the kernel reads
+// three keys per kLongRun/2 positions instead of three per position.
 __global__ __launch_bounds__(256) void long_find_kernel(const uint32_t *sk, uint32_t n, Header *hdr,
                                                         uint32_t *long_slot, uint32_t *long_head,
                                                         uint32_t max_slots)
 {
+    static_assert(kLongRun % 2 == 0 && kLongRun >= 2, "the probe distance is half the threshold");
+    constexpr uint32_t H = kLongRun / 2;
     if (hdr->batch_bad) return;
     n = min(n, hdr->n_valid);
-    const uint32_t stride = gridDim.x * blockDim.x;
-    for (uint32_t p = blockIdx.x * blockDim.x + threadIdx.x; p + kLongRun < n; p += stride) {
-        const uint32_t x = sk[p];
-        if ((p == 0 || sk[p - 1] != x) && sk[p + kLongRun] == x) {
+    const uint32_t threads = gridDim.x * blockDim.x;
+    for (uint32_t t = blockIdx.x * blockDim.x + threadIdx.x; t < n / H; t += threads) {
+        const uint32_t q = t * H;                    // q + H <= n
+        if (q + H >= n) break;
+        const uint32_t x = sk[q];
+        if (sk[q + H] != x) continue;
+        if (q >= H && sk[q - H] == x) continue;      // not the first probed position inside its run
+        // the head lies in (q - H, q], or in [0, q] at the start of the batch: the first position whose key is x
+        uint32_t lo = q >= H ? q - H : 0xFFFFFFFFu, hi = q;      // sk[lo] != x (lo = -1: before the batch), sk[hi] == x
+        while (hi - lo > 1u) {                       // unsigned wrap-around makes -1 work: hi - lo = hi + 1
+            const uint32_t mid = lo + (hi - lo) / 2u;
+            if (sk[mid] == x) hi = mid; else lo = mid;
+        }
+        const uint32_t p = hi;
+        if (p + kLongRun < n && sk[p + kLongRun] == x) {
             const uint32_t slot = atomicAdd(&hdr->n_long, 1u);
             if (slot < max_slots) {          // always true: at most n / (kLongRun+1) such rows exist
                 long_head[slot] = p;
