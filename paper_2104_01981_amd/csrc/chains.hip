@@ -68,10 +68,16 @@ __global__ __launch_bounds__(256) void long_plan_kernel(const uint32_t *sk, uint
     for (uint32_t slot = wave_id(); slot < nl; slot += wave_count()) {
         const uint32_t p = uniform(long_head[slot]);
         const uint32_t x = uniform(sk[p]);
+        // the run's end, by a 64-ary search: the lanes probe 64 evenly spaced positions of (lo, hi] at once, and
+        // the probes that still carry x are a prefix of them (the keys are sorted)
         uint32_t lo = p + kLongRun, hi = n;            // sk[lo] == x, sk[hi] != x (hi == n: past the end)
         while (hi - lo > 1) {
-            const uint32_t mid = lo + (hi - lo) / 2;
-            if (uniform(sk[mid]) == x) lo = mid; else hi = mid;
+            const uint32_t step = (hi - lo + kWave - 1) / kWave;                 // >= 1
+            const uint32_t probe = lo + (lane + 1u) * step;                      // <= lo + 64 * step < 2^32: n <= 2^31
+            const uint32_t inside = (uint32_t)__popcll(__ballot(probe < hi && sk[probe] == x));
+            const uint32_t first_out = lo + (inside + 1u) * step;                // the first probe that is not x, if any
+            lo += inside * step;
+            if (inside < (uint32_t)kWave && first_out < hi) hi = first_out;
         }
         const uint32_t L = hi - p;
         if (L <= mid_max) {
