@@ -53,62 +53,97 @@ __global__ __launch_bounds__(256) void long_find_kernel(const uint32_t *sk, uint
 // Length of each long run (binary search for its end) and its cut into pieces.  One wave per run.
 // A run of at most mid_max updates gets no pieces: its slot goes on the list of its length class
 // (mid_chain_kernel) -- provided the batch has at least mid_min_rows long rows.
-__global__ __launch_bounds__(256) void long_plan_kernel(const uint32_t *sk, uint32_t n, Header *hdr,
-                                                        const uint32_t *long_head, uint32_t *long_len,
-                                                        uint32_t *long_piece, uint32_t *long_count,
-                                                        uint32_t *long_base, uint32_t *piece_slot,
-                                                        uint32_t *mid_list, uint32_t mid_max, uint32_t mid_min_rows,
-                                                        uint32_t max_slots, uint32_t max_pieces)
+constexpr int kPlanWaves = 16;      // runs a block of the plan kernel looks at together
+
+__global__ __launch_bounds__(kPlanWaves * kWave) void long_plan_kernel(
+    const uint32_t *sk, uint32_t n, Header *hdr, const uint32_t *long_head, uint32_t *long_len, uint32_t *long_piece,
+    uint32_t *long_count, uint32_t *long_base, uint32_t *piece_slot, uint32_t *mid_list, uint32_t mid_max,
+    uint32_t mid_min_rows, uint32_t max_slots, uint32_t max_pieces)
 {
+    // what each wave found, and where its run's pieces (or its place in a list) begin
+    __shared__ uint32_t s_pieces[kPlanWaves], s_len[kPlanWaves], s_class[kPlanWaves], s_start[kPlanWaves];
+    constexpr uint32_t kNoClass = 0xFFFFFFFFu;
     if (hdr->batch_bad) return;
     n = min(n, hdr->n_valid);
     const uint32_t nl = min(hdr->n_long, max_slots);
     if (nl < mid_min_rows) mid_max = 0;
-    const uint32_t lane = lane_id();
-    for (uint32_t slot = wave_id(); slot < nl; slot += wave_count()) {
-        const uint32_t p = uniform(long_head[slot]);
-        const uint32_t x = uniform(sk[p]);
-        // the run's end, by a 64-ary search: the lanes probe 64 evenly spaced positions of (lo, hi] at once, and
-        // the probes that still carry x are a prefix of them (the keys are sorted)
-        uint32_t lo = p + kLongRun, hi = n;            // sk[lo] == x, sk[hi] != x (hi == n: past the end)
-        while (hi - lo > 1) {
-            const uint32_t step = (hi - lo + kWave - 1) / kWave;                 // >= 1
-            const uint32_t probe = lo + (lane + 1u) * step;                      // <= lo + 64 * step < 2^32: n <= 2^31
-            const uint32_t inside = (uint32_t)__popcll(__ballot(probe < hi && sk[probe] == x));
-            const uint32_t first_out = lo + (inside + 1u) * step;                // the first probe that is not x, if any
-            lo += inside * step;
-            if (inside < (uint32_t)kWave && first_out < hi) hi = first_out;
-        }
-        const uint32_t L = hi - p;
-        if (L <= mid_max) {
-            if (lane == 0) {
-                uint32_t c = 0;
-                while (c + 1 < kMidClasses && ((L - 1) / kLongRun) >> (c + 1)) ++c;
-                const uint32_t at = atomicAdd(&hdr->n_mid[c], 1u);
-                if (at < max_slots) mid_list[(size_t)c * max_slots + at] = slot;   // always true: at most n_long such rows
-                atomicAdd(&hdr->n_long_items, (unsigned long long)L);
-                long_len[slot] = L;
-                long_piece[slot] = 0;
-                long_count[slot] = 0;
-                long_base[slot] = 0;
+    const uint32_t lane = lane_id(), w = uniform(threadIdx.x / kWave);
+    for (uint32_t slot0 = blockIdx.x * kPlanWaves; slot0 < nl; slot0 += gridDim.x * kPlanWaves) {
+        const uint32_t slot = slot0 + w;
+        uint32_t L = 0, C = 0, P = 0, cls = kNoClass;
+        if (slot < nl) {
+            const uint32_t p = uniform(long_head[slot]);
+            const uint32_t x = uniform(sk[p]);
+            // the run's end, by a 64-ary search: the lanes probe 64 evenly spaced positions of (lo, hi] at once, and
+            // the probes that still carry x are a prefix of them (the keys are sorted)
+            uint32_t lo = p + kLongRun, hi = n;            // sk[lo] == x, sk[hi] != x (hi == n: past the end)
+            while (hi - lo > 1) {
+                const uint32_t step = (hi - lo + kWave - 1) / kWave;                 // >= 1
+                const uint32_t probe = lo + (lane + 1u) * step;                      // <= lo + 64 * step < 2^32: n <= 2^31
+                const uint32_t inside = (uint32_t)__popcll(__ballot(probe < hi && sk[probe] == x));
+                const uint32_t first_out = lo + (inside + 1u) * step;                // the first probe that is not x, if any
+                lo += inside * step;
+                if (inside < (uint32_t)kWave && first_out < hi) hi = first_out;
             }
-            continue;
+            L = hi - p;
+            if (L <= mid_max) {
+                cls = 0;
+                while (cls + 1 < kMidClasses && ((L - 1) / kLongRun) >> (cls + 1)) ++cls;
+            } else {
+                C = (L + kPieceMaxCount - 1) / kPieceMaxCount;
+                if (C < kPieceMin) C = kPieceMin;
+                P = (L + C - 1) / C;
+            }
         }
-        uint32_t C = (L + kPieceMaxCount - 1) / kPieceMaxCount;
-        if (C < kPieceMin) C = kPieceMin;
-        const uint32_t P = (L + C - 1) / C;
-        uint32_t base = 0;
         if (lane == 0) {
-            base = atomicAdd(&hdr->n_pieces, P);
-            atomicAdd(&hdr->n_long_items, (unsigned long long)L);
-            long_len[slot] = L;
-            long_piece[slot] = C;
-            long_count[slot] = P;
-            long_base[slot] = base;
+            s_pieces[w] = P;
+            s_len[w] = L;
+            s_class[w] = cls;
         }
-        base = uniform(base);
+        __syncthreads();
+        // One thread reserves for the whole block: the counters are updated once per kPlanWaves runs (one update
+        // per run kept this kernel at the pace of the counters: 11 000 updates of three addresses, 94 us).
+        if (threadIdx.x == 0) {
+            uint32_t pieces = 0, in_class[kMidClasses];
+            unsigned long long items = 0;
+#pragma unroll
+            for (uint32_t c = 0; c < kMidClasses; ++c) in_class[c] = 0;
+#pragma unroll
+            for (int v = 0; v < kPlanWaves; ++v) {
+                pieces += s_pieces[v];
+                items += s_len[v];
+#pragma unroll
+                for (uint32_t c = 0; c < kMidClasses; ++c) in_class[c] += s_class[v] == c ? 1u : 0u;
+            }
+            uint32_t piece_at = pieces ? atomicAdd(&hdr->n_pieces, pieces) : 0u;
+            if (items) atomicAdd(&hdr->n_long_items, items);
+            uint32_t class_at[kMidClasses];
+#pragma unroll
+            for (uint32_t c = 0; c < kMidClasses; ++c) class_at[c] = in_class[c] ? atomicAdd(&hdr->n_mid[c], in_class[c]) : 0u;
+#pragma unroll
+            for (int v = 0; v < kPlanWaves; ++v) {
+                uint32_t start = piece_at;
+                piece_at += s_pieces[v];
+#pragma unroll
+                for (uint32_t c = 0; c < kMidClasses; ++c) {
+                    if (s_class[v] == c) start = class_at[c]++;
+                }
+                s_start[v] = start;
+            }
+        }
+        __syncthreads();
+        const uint32_t start = s_start[w];
+        __syncthreads();                                   // s_* are free for the next round
+        if (slot >= nl) continue;
+        if (lane == 0) {
+            long_len[slot] = L;
+            long_piece[slot] = C;                          // 0: no pieces, one workgroup walks the run
+            long_count[slot] = P;
+            long_base[slot] = P ? start : 0u;
+            if (cls != kNoClass && start < max_slots) mid_list[(size_t)cls * max_slots + start] = slot;   // always true: at most n_long such rows
+        }
         for (uint32_t j = lane; j < P; j += kWave)
-            if (base + j < max_pieces) piece_slot[base + j] = slot;   // always true by the bound on pieces
+            if (start + j < max_pieces) piece_slot[start + j] = slot;   // always true by the bound on pieces
     }
 }
 
@@ -560,8 +595,9 @@ static void chains_for(const Scratch &s, const Geometry &g, const LaunchGrids &l
     const dim3 grid(cus * 8), block(256);
     hipLaunchKernelGGL(long_find_kernel, grid, block, 0, st, sk, n, s.hdr, s.long_slot, s.long_head, max_slots);
     const uint32_t mid_max = MODE == kAdagradSeq ? kMidMax : 0u;     // the other rules read a long run once anyway
-    hipLaunchKernelGGL(long_plan_kernel, grid, block, 0, st, sk, n, s.hdr, s.long_head, s.long_len, s.long_piece,
-                       s.long_count, s.long_base, s.piece_slot, s.mid_list, mid_max, lg.mid_min_rows, max_slots, max_pieces);
+    hipLaunchKernelGGL(long_plan_kernel, dim3(cus * 2), dim3(kPlanWaves * kWave), 0, st, sk, n, s.hdr, s.long_head, s.long_len,
+                       s.long_piece, s.long_count, s.long_base, s.piece_slot, s.mid_list, mid_max, lg.mid_min_rows, max_slots,
+                       max_pieces);
     if (mid_max > kLongRun && n / (kLongRun + 1u) >= lg.mid_min_rows)       // else the plan kernel lists no such run
         hipLaunchKernelGGL((mid_chain_kernel<NC>), dim3(lg.mid), dim3(kMidWaves * kWave), 0, st, sk, si, grads, A, s.hdr,
                            s.long_head, s.long_len, s.mid_list, s.long_res, max_slots, g);
