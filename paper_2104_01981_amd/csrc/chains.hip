@@ -58,7 +58,7 @@ constexpr int kPlanWaves = 16;      // runs a block of the plan kernel looks at 
 __global__ __launch_bounds__(kPlanWaves * kWave) void long_plan_kernel(
     const uint32_t *sk, uint32_t n, Header *hdr, const uint32_t *long_head, uint32_t *long_len, uint32_t *long_piece,
     uint32_t *long_count, uint32_t *long_base, uint32_t *piece_slot, uint32_t *mid_list, uint32_t mid_max,
-    uint32_t mid_min_rows, uint32_t max_slots, uint32_t max_pieces)
+    uint32_t mid_min_rows, uint32_t piece_waves, uint32_t max_slots, uint32_t max_pieces)
 {
     // what each wave found, and where its run's pieces (or its place in a list) begin
     __shared__ uint32_t s_pieces[kPlanWaves], s_len[kPlanWaves], s_class[kPlanWaves], s_start[kPlanWaves];
@@ -67,6 +67,12 @@ __global__ __launch_bounds__(kPlanWaves * kWave) void long_plan_kernel(
     n = min(n, hdr->n_valid);
     const uint32_t nl = min(hdr->n_long, max_slots);
     if (nl < mid_min_rows) mid_max = 0;
+    // Smallest piece: a piece costs its wave a few memory latencies before the first gradient arrives, so pieces
+    // should be as long as the work allows while there are still several per wave of the piece kernels.  How much
+    // work there is is not known yet; the number of long rows is, and such a row has kLongRowGuess updates on
+    // average in the skewed batches this path exists for (measured optimum: 256-512 with 420 long rows in 2^24
+    // updates, >= 2048 with 3801 in 2^26).
+    const uint32_t piece_min = min(kPieceMinCap, max(kPieceMin, (uint32_t)((unsigned long long)nl * kLongRowGuess / piece_waves)));
     const uint32_t lane = lane_id(), w = uniform(threadIdx.x / kWave);
     for (uint32_t slot0 = blockIdx.x * kPlanWaves; slot0 < nl; slot0 += gridDim.x * kPlanWaves) {
         const uint32_t slot = slot0 + w;
@@ -91,7 +97,7 @@ __global__ __launch_bounds__(kPlanWaves * kWave) void long_plan_kernel(
                 while (cls + 1 < kMidClasses && ((L - 1) / kLongRun) >> (cls + 1)) ++cls;
             } else {
                 C = (L + kPieceMaxCount - 1) / kPieceMaxCount;
-                if (C < kPieceMin) C = kPieceMin;
+                if (C < piece_min) C = piece_min;
                 P = (L + C - 1) / C;
             }
         }
@@ -596,8 +602,8 @@ static void chains_for(const Scratch &s, const Geometry &g, const LaunchGrids &l
     hipLaunchKernelGGL(long_find_kernel, grid, block, 0, st, sk, n, s.hdr, s.long_slot, s.long_head, max_slots);
     const uint32_t mid_max = MODE == kAdagradSeq ? kMidMax : 0u;     // the other rules read a long run once anyway
     hipLaunchKernelGGL(long_plan_kernel, dim3(cus * 2), dim3(kPlanWaves * kWave), 0, st, sk, n, s.hdr, s.long_head, s.long_len,
-                       s.long_piece, s.long_count, s.long_base, s.piece_slot, s.mid_list, mid_max, lg.mid_min_rows, max_slots,
-                       max_pieces);
+                       s.long_piece, s.long_count, s.long_base, s.piece_slot, s.mid_list, mid_max, lg.mid_min_rows,
+                       (uint32_t)lg.p1 * (256u / kWave), max_slots, max_pieces);
     if (mid_max > kLongRun && n / (kLongRun + 1u) >= lg.mid_min_rows)       // else the plan kernel lists no such run
         hipLaunchKernelGGL((mid_chain_kernel<NC>), dim3(lg.mid), dim3(kMidWaves * kWave), 0, st, sk, si, grads, A, s.hdr,
                            s.long_head, s.long_len, s.mid_list, s.long_res, max_slots, g);

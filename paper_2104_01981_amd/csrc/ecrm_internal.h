@@ -29,7 +29,9 @@ constexpr int kMaxBins = 1 << kMaxRadixBits;
 // shorter runs are walked by one wave inside the apply kernel (read once, but at one wave's pace).
 // Measured: 256 -> 1024 takes 6 % off the Zipf-only workload and 0.5 % off the mixed one; 2048 loses.
 constexpr uint32_t kLongRun = ECRM_LONG_RUN;
-constexpr uint32_t kPieceMin = 128;  // smallest chain piece
+constexpr uint32_t kPieceMin = 128;  // smallest chain piece (what the scratch buffer is sized for) ...
+constexpr uint32_t kPieceMinCap = 2048;   // ... and the largest value the plan kernel raises that minimum to
+constexpr uint32_t kLongRowGuess = 6144;  // updates a long row is taken to have when the piece size is chosen
 constexpr uint32_t kPieceMaxCount = 1024;     // a chain is cut into at most this many pieces
 // Adagrad runs of more than kLongRun and at most kMidMax updates are walked by ONE workgroup that keeps the
 // gradients in registers between the sum of squares and the steps (one read); only longer runs, which need
