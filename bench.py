@@ -27,10 +27,10 @@ LONG_RUN = 1024          # ECRM_LONG_RUN of include/ecrm.h: longer runs leave th
 # HBM bytes per launch of the apply kernel, from rocprofv3 FETCH_SIZE and WRITE_SIZE scaled by a plain copy of known
 # size (profiles/update_path_<workload>_hbm_traffic.txt).  Reported only while the code of the kernel's sources is
 # what the counters were taken on.
-TRAFFIC_BYTES_PER_LAUNCH = {"hbm_scale": 37956103855, "large_uniform": 77514013050, "large_skewed": 42551274313}
+TRAFFIC_BYTES_PER_LAUNCH = {"hbm_scale": 37956210358, "large_uniform": 77511610801, "large_skewed": 42551350805}
 TRAFFIC_SOURCES = ["paper_2104_01981_amd/csrc/update.hip", "paper_2104_01981_amd/csrc/rows.h",
                    "paper_2104_01981_amd/csrc/ecrm_internal.h"]
-TRAFFIC_SOURCES_SHA256 = "0f9b4aaa403de8c3efdd094dfbc66ec4a6daecfd5316f84c811da1cc7b64c729"
+TRAFFIC_SOURCES_SHA256 = "0d2d60c869f179fb6dab8074dd53f02feb9a25a1b3a818c79621c76953355bf3"
 
 
 def code_digest(paths):
