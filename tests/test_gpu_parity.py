@@ -259,14 +259,20 @@ def test_profile_hooks():
     assert c.ctx.profile_read()[1] == 0
 
 
-def test_update_inside_a_hip_graph():
+@pytest.mark.parametrize("n", [20000, 300000])
+def test_update_inside_a_hip_graph(n):
     """ecrm_update only enqueues kernels (no memsets, no synchronisation), so a caller may capture it.
-    Replays are checked one by one against eager calls on a twin, with eager work in between."""
-    R, D, k, S, n = 4 * 2000, 128, 4, 5, 20000
+    Replays are checked one by one against eager calls on a twin, with eager work in between.  The larger batch
+    brings the kernels of large batches into the graph: the list of groups, and (tuned in) the one-workgroup chains."""
+    R, D, k, S = 4 * 2000, 128, 4, 5
     a = Case(R, D, k, S, max_batch=n, seed=71)
     b = Case(R, D, k, S, max_batch=n, seed=71)
     keys = si.uniform_keys(71, 0, n, R)
-    keys[::7] = 4321                                   # a long run as well
+    keys[::7] = 4321                                   # a long run as well (42 857 updates in the larger batch: pieces)
+    if n > 100000:
+        keys[1::61] = 999                              # ~4 900 updates: one workgroup
+        a.ctx.tune(TUNE_MID_MIN_ROWS, 1)
+        b.ctx.tune(TUNE_MID_MIN_ROWS, 1)
     kt = torch.from_numpy(keys.view(np.int64)).cuda()
     g = grads_for(71, 0, n, D)
     a.ctx.update(kt, g)                                # warm-up outside the capture (first-call set-up)
@@ -287,6 +293,9 @@ def test_update_inside_a_hip_graph():
     torch.cuda.synchronize()
     assert torch.equal(a.E, b.E) and torch.equal(a.PA, b.PA)
     assert a.ctx.status() == 0
+    if n > 100000:
+        stats = a.ctx.batch_stats()
+        assert stats["long_rows"] == 2 and stats["one_workgroup_rows"] == 1 and stats["pieces"] > 0
 
 
 def test_row_traffic_probe():
